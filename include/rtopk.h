@@ -1,0 +1,143 @@
+/*
+ * rtopk -- batched radix top-k selection on AMD Instinct MI355X (gfx950).
+ *
+ * C ABI.  Plain pointers and sizes only; no exceptions cross the boundary; no
+ * global state apart from an immutable tuning default.  Every pointer named
+ * "device" is GPU memory (hipMalloc or a PyTorch CUDA/HIP tensor's data_ptr()),
+ * everything else is host memory.
+ *
+ * The operation (paper, Section 1: top-k of n elements, values and their
+ * positions, largest or smallest, any k <= n; Section 2.3.1, Algorithm 1: radix
+ * select of the k-th element followed by a filter; Section 2.3.2 / 3.2: a batch
+ * of B independent tasks):
+ *
+ *   for every row r of keys[batch][n]:
+ *     choose the k elements that rank best under the order
+ *         NaN (any sign/payload) > +inf > ... > +0 > -0 > ... > -inf      (largest)
+ *       or its reverse                                                    (smallest),
+ *     ties at the k-th key resolved towards the LOWEST index,
+ *     and write their original bit patterns and their positions in the row.
+ *
+ * The selected SET is unique and reproducible.  The order of the k outputs
+ * inside a row is unspecified (the paper's output is unsorted, Section 2.3.1);
+ * it is, however, the same on every run with the same arguments.
+ */
+#ifndef RTOPK_H
+#define RTOPK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { RTOPK_F32 = 0, RTOPK_F16 = 1, RTOPK_BF16 = 2 } rtopk_dtype;
+
+typedef enum {
+    RTOPK_OK = 0,
+    RTOPK_ERR_INVALID_ARG = 1,          /* null pointer, k < 1, k > n, batch < 1, n out of range, bad dtype/flags */
+    RTOPK_ERR_WORKSPACE_TOO_SMALL = 2,  /* workspace_bytes below rtopk_workspace_bytes() for these arguments    */
+    RTOPK_ERR_UNSUPPORTED = 3,          /* misaligned buffers (see rtopk_select)                                */
+    RTOPK_ERR_HIP = 4                   /* a kernel launch was rejected by the runtime                          */
+} rtopk_status;
+
+enum {
+    /* Adaptive scaling (paper Section 4.3): one element a_s of each row is drawn with `seed` and
+     * subtracted (one fp32 rounding) from every element before digits are taken, which spreads
+     * the exponents of keys clustered near a_s.  The rounded difference orders keys weakly, so
+     * the library finishes the selection on the unscaled key; the result is identical with and
+     * without the flag and for every seed.  Ignored for 16-bit keys. */
+    RTOPK_FLAG_SCALING = 1u << 0
+};
+
+/* Maximum row length: indices are kept in 32 bits inside the library. */
+#define RTOPK_MAX_N ((int64_t)1 << 31)
+
+/*
+ * Optional tuning knobs.  The selected set never depends on them (the paper calls the digit
+ * width and block/grid sizes hyper-parameters, Section 5.2); tests use them to exercise every
+ * code path on the same input.  A field left 0 means "library default".
+ */
+typedef struct {
+    int32_t digit_bits;      /* radix digit width d, 4..12 (default 12 for fp32, 11 for 16-bit keys)           */
+    int32_t path;            /* 0 auto, 1 one workgroup per row (fused kernel), 2 many workgroups per row      */
+    int32_t wgs_per_row;     /* workgroups cooperating on one row in path 2 (default: fill 256 CUs)            */
+    int32_t small_threshold; /* candidate count at or below which one workgroup finishes a row by itself       */
+} rtopk_tuning;
+
+/*
+ * Size in bytes of the device scratch buffer rtopk_select needs for these arguments
+ * (two candidate arrays of n (value, index) pairs per row, per-workgroup histograms, per-row
+ * state -- the "workspace in global memory" of paper Section 2.2.3).  Host-only, launches nothing.
+ * `tuning` may be NULL.  Returns RTOPK_ERR_INVALID_ARG on bad arguments and leaves *bytes_out.
+ */
+rtopk_status rtopk_workspace_bytes(int64_t batch, int64_t n, int64_t k, rtopk_dtype dt, uint32_t flags,
+                                   const rtopk_tuning* tuning, size_t* bytes_out);
+
+/*
+ * Enqueue the selection on `hip_stream` (a hipStream_t; NULL = the default stream) and return
+ * without synchronising.  No memory is allocated or freed.  Nothing is read back to the host:
+ * loop control lives in the workspace (Algorithm 1's loop state, Section 2.3.1).
+ *
+ *   keys         device, [batch][n] row-major, element type dt, read-only.  The first row must
+ *                start on a multiple of the element size; rows need NOT be 16-byte aligned (loads
+ *                start at the aligned address at or before the row and mask the lead-in, the
+ *                paper's on-demand offset padding, Section 3.2.2).
+ *   batch, n, k  1 <= batch, 1 <= n <= RTOPK_MAX_N, 1 <= k <= n.
+ *   largest      non-zero: k largest; zero: k smallest.
+ *   flags        OR of RTOPK_FLAG_*; unknown bits are rejected.
+ *   seed         only drives the draw of a_s under RTOPK_FLAG_SCALING.
+ *   out_values   device, [batch][k], element type dt, aligned to the element size; receives the
+ *                selected elements' original bits (NaN payloads and zero signs preserved).
+ *   out_indices  device, [batch][k] int64, 8-byte aligned; position of each selected element in its row.
+ *   workspace    device, 256-byte aligned, at least rtopk_workspace_bytes(...) bytes computed with the
+ *                same batch, n, k, dt, flags and tuning.  Contents are undefined afterwards.  Two calls
+ *                that may overlap in time must not share a workspace.
+ *
+ * Errors are detected on the host before anything is launched; on error no output is written.
+ */
+rtopk_status rtopk_select(const void* keys, int64_t batch, int64_t n, int64_t k, rtopk_dtype dt, int largest,
+                          uint32_t flags, uint64_t seed, void* out_values, int64_t* out_indices,
+                          void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Same as rtopk_select with explicit tuning knobs (NULL = defaults). */
+rtopk_status rtopk_select_ex(const void* keys, int64_t batch, int64_t n, int64_t k, rtopk_dtype dt, int largest,
+                             uint32_t flags, uint64_t seed, void* out_values, int64_t* out_indices,
+                             void* workspace, size_t workspace_bytes, void* hip_stream,
+                             const rtopk_tuning* tuning);
+
+/*
+ * Per-pass record of the last rtopk_select that used `workspace`, for tests and profiling:
+ * which bin each digit pass chose and how many candidates and winners it left (the quantities
+ * selectBin and selectCandidate produce, paper Section 2.3.1).  The records live at the start of
+ * the workspace: row r's record is RTOPK_TRACE_STRIDE bytes at byte offset r * RTOPK_TRACE_STRIDE,
+ * laid out as rtopk_row_trace.  Read it with any device-to-host copy after the stream has drained.
+ */
+#define RTOPK_TRACE_STRIDE 512
+#define RTOPK_TRACE_MAX_PASSES 12
+typedef struct {
+    uint32_t k_rem, cand_count, out_count, pass, bin, emit_all, done, ticket, win_total, next_count;
+    float a_s;
+    uint32_t cur_buf, error, passes_run, reserved[2];
+    struct {
+        uint32_t bin;          /* chosen bin of this digit                                           */
+        uint32_t k_after;      /* rank of the k-th key inside the bin (0 if the whole bin was taken) */
+        uint32_t cand_after;   /* candidates passed on to the next digit                             */
+        uint32_t winners;      /* elements sent to the output by this pass                           */
+        uint32_t source;       /* 0 scaled key, 1 key, 2 index (tie break)                           */
+        uint32_t shift, bits;  /* digit window: bits [shift, shift + bits) of that source            */
+        uint32_t where;        /* 1 many workgroups, 2 single-workgroup finish, 3 fused row kernel   */
+    } pass_rec[RTOPK_TRACE_MAX_PASSES];
+} rtopk_row_trace;
+
+/* Static description of an error code. */
+const char* rtopk_status_string(rtopk_status status);
+
+/* Library version, "major.minor". */
+const char* rtopk_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RTOPK_H */

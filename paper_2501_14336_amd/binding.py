@@ -1,0 +1,184 @@
+"""ctypes binding of the C-ABI library (include/rtopk.h).
+
+Argument marshalling only: every step of the selection runs in the HIP kernels.
+PyTorch supplies device memory (``data_ptr()``) and the current stream.  There is
+no fallback: if the library is not built or no GPU is present, calls raise.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_ROOT = os.path.dirname(_HERE)
+_SRC_DIR = os.path.join(_HERE, "csrc")
+_LIB_PATH = os.path.join(_HERE, "librtopk.so")
+
+RTOPK_F32, RTOPK_F16, RTOPK_BF16 = 0, 1, 2
+RTOPK_OK = 0
+RTOPK_FLAG_SCALING = 1
+RTOPK_TRACE_STRIDE = 512
+RTOPK_TRACE_MAX_PASSES = 12
+
+EXPORTS = (
+    "rtopk_workspace_bytes",
+    "rtopk_select",
+    "rtopk_select_ex",
+    "rtopk_status_string",
+    "rtopk_version",
+)
+
+
+class RtopkTuning(ctypes.Structure):
+    _fields_ = [
+        ("digit_bits", ctypes.c_int32),
+        ("path", ctypes.c_int32),
+        ("wgs_per_row", ctypes.c_int32),
+        ("small_threshold", ctypes.c_int32),
+    ]
+
+
+class _PassRec(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_uint32) for n in
+                ("bin", "k_after", "cand_after", "winners", "source", "shift", "bits", "where")]
+
+
+class RtopkRowTrace(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_uint32) for n in
+                ("k_rem", "cand_count", "out_count", "pass_", "bin", "emit_all", "done", "ticket",
+                 "win_total", "next_count")] + [("a_s", ctypes.c_float)] + \
+               [(n, ctypes.c_uint32) for n in ("cur_buf", "error", "passes_run")] + \
+               [("reserved", ctypes.c_uint32 * 2), ("pass_rec", _PassRec * RTOPK_TRACE_MAX_PASSES)]
+
+
+class RtopkError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__("rtopk: %s (status %d)" % (message, status))
+        self.status = status
+
+
+def build(force: bool = True) -> str:
+    """Compile csrc/ for gfx950 into librtopk.so next to this file (hipcc cross-compiles without a GPU)."""
+    srcs = [os.path.join(_SRC_DIR, "rtopk_kernels.hip")]
+    deps = srcs + [os.path.join(_SRC_DIR, "rtopk_device.h"), os.path.join(_ROOT, "include", "rtopk.h")]
+    if not force and os.path.exists(_LIB_PATH) and all(os.path.getmtime(_LIB_PATH) >= os.path.getmtime(d) for d in deps):
+        return _LIB_PATH
+    tmp = _LIB_PATH + ".tmp%d" % os.getpid()
+    cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-I", os.path.join(_ROOT, "include"), "-I", _SRC_DIR, "-o", tmp] + srcs
+    subprocess.check_call(cmd)
+    os.replace(tmp, _LIB_PATH)
+    return _LIB_PATH
+
+
+_lib = None
+
+
+def load():
+    """Load librtopk.so (built beforehand; built now only if it is missing)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            build(force=True)
+        lib = ctypes.CDLL(_LIB_PATH)
+        i64, u32, u64, vp, sz = ctypes.c_int64, ctypes.c_uint32, ctypes.c_uint64, ctypes.c_void_p, ctypes.c_size_t
+        lib.rtopk_workspace_bytes.restype = ctypes.c_int
+        lib.rtopk_workspace_bytes.argtypes = [i64, i64, i64, ctypes.c_int, u32, ctypes.POINTER(RtopkTuning),
+                                              ctypes.POINTER(sz)]
+        lib.rtopk_select.restype = ctypes.c_int
+        lib.rtopk_select.argtypes = [vp, i64, i64, i64, ctypes.c_int, ctypes.c_int, u32, u64, vp, vp, vp, sz, vp]
+        lib.rtopk_select_ex.restype = ctypes.c_int
+        lib.rtopk_select_ex.argtypes = lib.rtopk_select.argtypes + [ctypes.POINTER(RtopkTuning)]
+        lib.rtopk_status_string.restype = ctypes.c_char_p
+        lib.rtopk_status_string.argtypes = [ctypes.c_int]
+        lib.rtopk_version.restype = ctypes.c_char_p
+        lib.rtopk_version.argtypes = []
+        _lib = lib
+    return _lib
+
+
+def rtopk_status_string(status: int) -> str:
+    return load().rtopk_status_string(int(status)).decode()
+
+
+def rtopk_version() -> str:
+    return load().rtopk_version().decode()
+
+
+def _tuning_ptr(tuning):
+    if tuning is None:
+        return None
+    if isinstance(tuning, dict):
+        tuning = RtopkTuning(**tuning)
+    return ctypes.byref(tuning)
+
+
+def rtopk_workspace_bytes(batch: int, n: int, k: int, dtype: int, flags: int = 0, tuning=None) -> int:
+    out = ctypes.c_size_t(0)
+    st = load().rtopk_workspace_bytes(batch, n, k, dtype, flags, _tuning_ptr(tuning), ctypes.byref(out))
+    if st != RTOPK_OK:
+        raise RtopkError(st, rtopk_status_string(st))
+    return int(out.value)
+
+
+def rtopk_select(keys_ptr: int, batch: int, n: int, k: int, dtype: int, largest: bool, flags: int, seed: int,
+                 out_values_ptr: int, out_indices_ptr: int, workspace_ptr: int, workspace_bytes: int,
+                 stream: int = 0, tuning=None) -> None:
+    """Raw call: device addresses in, nothing allocated, nothing synchronised."""
+    st = load().rtopk_select_ex(keys_ptr, batch, n, k, dtype, 1 if largest else 0, flags, seed, out_values_ptr,
+                                out_indices_ptr, workspace_ptr, workspace_bytes, stream, _tuning_ptr(tuning))
+    if st != RTOPK_OK:
+        raise RtopkError(st, rtopk_status_string(st))
+
+
+# ---------------------------------------------------------------------------
+# torch conveniences (memory and stream plumbing only)
+# ---------------------------------------------------------------------------
+
+def _torch_dtype_code(t):
+    import torch
+    return {torch.float32: RTOPK_F32, torch.float16: RTOPK_F16, torch.bfloat16: RTOPK_BF16}[t.dtype]
+
+
+def topk(x, k: int, largest: bool = True, scaling: bool = False, seed: int = 0, tuning=None, workspace=None,
+         out=None):
+    """Top-k of every row of a CUDA/HIP tensor ``x`` ([n] or [batch, n]; fp32, fp16 or bf16).
+
+    Returns (values [batch, k] of x.dtype, indices [batch, k] int64, workspace).  The order inside a row is
+    unspecified.  ``workspace`` (a uint8 tensor) and ``out`` (a (values, indices) pair) are reused if given.
+    """
+    import torch
+    if not x.is_cuda:
+        raise RtopkError(1, "input tensor must live on the GPU; there is no CPU path")
+    if x.dim() == 1:
+        x = x[None, :]
+    if x.dim() != 2 or not x.is_contiguous():
+        raise RtopkError(1, "input must be a contiguous [batch, n] tensor")
+    batch, n = x.shape
+    code = _torch_dtype_code(x)
+    flags = RTOPK_FLAG_SCALING if scaling else 0
+    need = rtopk_workspace_bytes(batch, n, k, code, flags, tuning)
+    if workspace is None or workspace.numel() < need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    if out is None:
+        vals = torch.empty((batch, k), dtype=x.dtype, device=x.device)
+        idx = torch.empty((batch, k), dtype=torch.int64, device=x.device)
+    else:
+        vals, idx = out
+    stream = torch.cuda.current_stream(x.device).cuda_stream
+    rtopk_select(x.data_ptr(), batch, n, k, code, largest, flags, seed, vals.data_ptr(), idx.data_ptr(),
+                 workspace.data_ptr(), workspace.numel(), stream, tuning)
+    return vals, idx, workspace
+
+
+def read_trace(workspace, batch: int):
+    """Per-row pass records of the last call that used ``workspace`` (synchronises)."""
+    import numpy as np
+    raw = workspace[: batch * RTOPK_TRACE_STRIDE].cpu().numpy().tobytes()
+    out = []
+    for r in range(batch):
+        t = RtopkRowTrace.from_buffer_copy(raw[r * RTOPK_TRACE_STRIDE: r * RTOPK_TRACE_STRIDE + ctypes.sizeof(RtopkRowTrace)])
+        out.append(t)
+    return out
