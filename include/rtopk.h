@@ -113,21 +113,25 @@ rtopk_status rtopk_select_ex(const void* keys, int64_t batch, int64_t n, int64_t
  * selectBin and selectCandidate produce, paper Section 2.3.1).  The records live at the start of
  * the workspace: row r's record is RTOPK_TRACE_STRIDE bytes at byte offset r * RTOPK_TRACE_STRIDE,
  * laid out as rtopk_row_trace.  Read it with any device-to-host copy after the stream has drained.
+ * The library keeps its loop state in these records (each is written once per call).
  */
 #define RTOPK_TRACE_STRIDE 512
 #define RTOPK_TRACE_MAX_PASSES 12
 typedef struct {
-    uint32_t k_rem, cand_count, out_count, pass, bin, emit_all, done, ticket, win_total, next_count;
-    float a_s;
-    uint32_t cur_buf, error, passes_run, reserved[2];
+    float a_s;                 /* the element subtracted under RTOPK_FLAG_SCALING (0 if unused)      */
+    uint32_t error;            /* 0, or a bit set if the device saw an impossible state              */
+    uint32_t reserved[14];
     struct {
+        uint32_t where;        /* 0 pass not run; 1 many workgroups; 2 single-workgroup finish;
+                                  3 fused one-workgroup-per-row kernel                               */
         uint32_t bin;          /* chosen bin of this digit                                           */
         uint32_t k_after;      /* rank of the k-th key inside the bin (0 if the whole bin was taken) */
-        uint32_t cand_after;   /* candidates passed on to the next digit                             */
+        uint32_t cand_after;   /* candidates passed on to the next digit (0: the row is finished)    */
         uint32_t winners;      /* elements sent to the output by this pass                           */
-        uint32_t source;       /* 0 scaled key, 1 key, 2 index (tie break)                           */
-        uint32_t shift, bits;  /* digit window: bits [shift, shift + bits) of that source            */
-        uint32_t where;        /* 1 many workgroups, 2 single-workgroup finish, 3 fused row kernel   */
+        uint32_t out_before;   /* outputs already written when this pass started                     */
+        uint32_t cand_before;  /* candidates this pass looked at                                     */
+        uint32_t window;       /* source | shift << 8 | bits << 16; source 0 scaled key, 1 key,
+                                  2 index (tie break); the digit is bits [shift, shift + bits)       */
     } pass_rec[RTOPK_TRACE_MAX_PASSES];
 } rtopk_row_trace;
 

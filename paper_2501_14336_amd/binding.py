@@ -41,15 +41,39 @@ class RtopkTuning(ctypes.Structure):
 
 class _PassRec(ctypes.Structure):
     _fields_ = [(n, ctypes.c_uint32) for n in
-                ("bin", "k_after", "cand_after", "winners", "source", "shift", "bits", "where")]
+                ("where", "bin", "k_after", "cand_after", "winners", "out_before", "cand_before", "window")]
+
+    @property
+    def source(self):
+        return self.window & 0xFF
+
+    @property
+    def shift(self):
+        return (self.window >> 8) & 0xFF
+
+    @property
+    def bits(self):
+        return (self.window >> 16) & 0xFF
 
 
 class RtopkRowTrace(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_uint32) for n in
-                ("k_rem", "cand_count", "out_count", "pass_", "bin", "emit_all", "done", "ticket",
-                 "win_total", "next_count")] + [("a_s", ctypes.c_float)] + \
-               [(n, ctypes.c_uint32) for n in ("cur_buf", "error", "passes_run")] + \
-               [("reserved", ctypes.c_uint32 * 2), ("pass_rec", _PassRec * RTOPK_TRACE_MAX_PASSES)]
+    _fields_ = [("a_s", ctypes.c_float), ("error", ctypes.c_uint32), ("reserved", ctypes.c_uint32 * 14),
+                ("pass_rec", _PassRec * RTOPK_TRACE_MAX_PASSES)]
+
+    @property
+    def passes(self):
+        """Records of the passes that ran, in order."""
+        out = []
+        for r in self.pass_rec:
+            if r.where == 0:
+                break
+            out.append(r)
+        return out
+
+    @property
+    def done(self):
+        ps = self.passes
+        return bool(ps) and ps[-1].cand_after == 0
 
 
 class RtopkError(RuntimeError):

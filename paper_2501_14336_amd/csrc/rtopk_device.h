@@ -29,7 +29,7 @@ struct Params {
     void* out_values;        // Y values, [batch][k]
     long long* out_indices;  // Y indices, [batch][k]
     rtopk_row_trace* state;  // per-row loop state + trace, stride RTOPK_TRACE_STRIDE bytes
-    u32* ghist;              // [batch][kMaxBins]   global histogram of the current pass
+    u32* ghist;              // [2][batch][kMaxBins]  global histogram, one buffer per pass parity
     u32* bases;              // [batch][G][2]       per-workgroup output / candidate write offsets
     u32* swg;                // [batch][G][kSwgStride]  per-workgroup suffix sums of its local histogram
     uint2* cand[2];          // [batch][n]          (raw bits, index) candidates, ping-pong
@@ -122,6 +122,14 @@ __device__ __forceinline__ u32 digit_of(const PassInfo pi, u32 raw, u32 idx, u32
 // so that every load instruction of a wave covers 1 KiB of consecutive addresses.
 // ------------------------------------------------------------------------------------------------
 
+// Registers of one lane's share of a tile.
+template <int V>
+struct TileRegs {
+    uint4 r[V];
+    u32 e0[V];  // index of element 0 of each vector (row index for X, position for candidates)
+    bool full;  // every element of the tile is valid
+};
+
 // The input row X.  Loads start at the 16-byte aligned address at or before the row's first element
 // and elements outside [0, n) are masked (on-demand offset padding, Section 3.2.2).
 template <int DT, int B, int V>
@@ -130,14 +138,12 @@ struct KeySource {
     static constexpr int E = 16 / kElemBytes;  // elements per vector
     static constexpr int kSlots = V * E;       // elements per lane per tile
     static constexpr int kTileVecs = B * V;
+    typedef TileRegs<V> Tile;
 
     const uint4* abase;
     u32 lead;  // elements between abase and the row's first element
     u32 n;
     u64 nvec;  // vectors covering [abase, row end)
-    uint4 r[V];
-    u32 e0[V];  // row index of element 0 of each vector (wraps below 0 in the lead-in)
-    bool full;  // every element of the tile lies inside the row
 
     __device__ __forceinline__ void init(const void* keys, long long n_, int row) {
         const char* p = (const char*)keys + (size_t)row * (size_t)n_ * kElemBytes;
@@ -148,24 +154,24 @@ struct KeySource {
         nvec = ((u64)lead + (u64)n + E - 1) / E;
     }
     __device__ __forceinline__ u32 ntiles() const { return (u32)((nvec + kTileVecs - 1) / kTileVecs); }
-    __device__ __forceinline__ void load(u32 tile, u32 tid) {
+    __device__ __forceinline__ void load(u32 tile, u32 tid, Tile& t) const {
         u64 v0 = (u64)tile * kTileVecs;
-        full = (tile != 0 || lead == 0) && ((v0 + kTileVecs) * E <= (u64)lead + (u64)n);
+        t.full = (tile != 0 || lead == 0) && ((v0 + kTileVecs) * E <= (u64)lead + (u64)n);
 #pragma unroll
         for (int u = 0; u < V; ++u) {
             u64 v = v0 + (u64)u * B + tid;
-            e0[u] = (u32)(v * E) - lead;
-            if (full || v < nvec)
-                r[u] = abase[v];
+            t.e0[u] = (u32)(v * E) - lead;
+            if (t.full || v < nvec)
+                t.r[u] = abase[v];
             else
-                r[u] = make_uint4(0, 0, 0, 0);
+                t.r[u] = make_uint4(0, 0, 0, 0);
         }
     }
-    __device__ __forceinline__ void get(int s, u32& raw, u32& idx, bool& valid) const {
+    __device__ __forceinline__ void get(const Tile& t, int s, u32& raw, u32& idx, bool& valid) const {
         const int u = s / E, j = s % E;
-        idx = e0[u] + j;
-        valid = full || idx < n;  // lead-in wraps to huge values, vectors past the end start at >= n
-        const uint4 q = r[u];
+        idx = t.e0[u] + j;
+        valid = t.full || idx < n;  // the lead-in wraps to huge values, vectors past the end start at >= n
+        const uint4 q = t.r[u];
         if (E == 4) {
             raw = j == 0 ? q.x : j == 1 ? q.y : j == 2 ? q.z : q.w;
         } else {
@@ -182,13 +188,11 @@ struct CandSource {
     static constexpr int E = 2;
     static constexpr int kSlots = V * E;
     static constexpr int kTileVecs = B * V;
+    typedef TileRegs<V> Tile;
 
     const uint4* base;
     u32 count;
     u64 nvec;
-    uint4 r[V];
-    u32 p0[V];  // position of element 0 of each vector
-    bool full;
 
     __device__ __forceinline__ void init(const uint2* c, u32 count_) {
         base = (const uint4*)c;
@@ -196,24 +200,24 @@ struct CandSource {
         nvec = ((u64)count_ + 1) / 2;
     }
     __device__ __forceinline__ u32 ntiles() const { return (u32)((nvec + kTileVecs - 1) / kTileVecs); }
-    __device__ __forceinline__ void load(u32 tile, u32 tid) {
+    __device__ __forceinline__ void load(u32 tile, u32 tid, Tile& t) const {
         u64 v0 = (u64)tile * kTileVecs;
-        full = (v0 + kTileVecs) * E <= (u64)count;
+        t.full = (v0 + kTileVecs) * E <= (u64)count;
 #pragma unroll
         for (int u = 0; u < V; ++u) {
             u64 v = v0 + (u64)u * B + tid;
-            p0[u] = (u32)(v * E);
-            if (full || v < nvec)
-                r[u] = base[v];
+            t.e0[u] = (u32)(v * E);
+            if (t.full || v < nvec)
+                t.r[u] = base[v];
             else
-                r[u] = make_uint4(0, 0, 0, 0);
+                t.r[u] = make_uint4(0, 0, 0, 0);
         }
     }
-    __device__ __forceinline__ void get(int s, u32& raw, u32& idx, bool& valid) const {
+    __device__ __forceinline__ void get(const Tile& t, int s, u32& raw, u32& idx, bool& valid) const {
         const int u = s / E, j = s % E;
-        valid = full || (p0[u] + j) < count;
-        raw = j ? r[u].z : r[u].x;
-        idx = j ? r[u].w : r[u].y;
+        valid = t.full || (t.e0[u] + j) < count;
+        raw = j ? t.r[u].z : t.r[u].x;
+        idx = j ? t.r[u].w : t.r[u].y;
     }
 };
 
@@ -237,6 +241,26 @@ __device__ __forceinline__ u32 block_inclusive_scan(u32 v, u32* wsum) {
     for (u32 w = 0; w < wave; ++w) add += wsum[w];
     __syncthreads();
     return v + add;
+}
+
+// Sums of a and b over the workgroup, returned to every thread.  red: LDS, 2 * B/64 words.  Contains barriers.
+template <int B>
+__device__ __forceinline__ void block_sum2(u32& a, u32& b, u32* red) {
+    const u32 lane = lane_id();
+    const u32 wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        a += __shfl_down(a, o, 64);
+        b += __shfl_down(b, o, 64);
+    }
+    if (lane == 0) { red[2 * wave] = a; red[2 * wave + 1] = b; }
+    __syncthreads();
+    u32 sa = 0, sb = 0;
+#pragma unroll
+    for (int w = 0; w < B / 64; ++w) { sa += red[2 * w]; sb += red[2 * w + 1]; }
+    __syncthreads();
+    a = sa;
+    b = sb;
 }
 
 // In place: h[j] <- sum of h[i] for i >= j  (number of candidates whose digit is at least j).

@@ -31,137 +31,128 @@ namespace rtopk {
 
 constexpr int kGridBlock = 512;   // threads per workgroup, many-workgroups-per-row kernels
 constexpr int kRowBlock = 1024;   // threads per workgroup, one-workgroup-per-row kernels
-constexpr int kVecs = 4;          // 16-byte loads in flight per lane
+constexpr int kVecs = 4;          // 16-byte loads per lane per tile
 
 template <int B>
 struct Shared {
     u32 hist[kMaxBins];
     u32 wsum[B / 64];
+    u32 red[2 * (B / 64)];
     u32 wcnt[2][B / 64][2];
     u32 sel;
-    u32 flag;
-    u32 carry[2];
 };
 
+// Loop state on entry to pass p (Algorithm 1's candidates / k, plus the output fill level).
+struct PassEntry {
+    u32 cand;        // candidates entering the pass (n for the first pass)
+    u32 k_rem;       // how many of them are still wanted
+    u32 out_before;  // outputs already written
+    bool finished;   // an earlier pass completed the row
+    bool prev_multi; // the previous pass was run by the many-workgroup kernels
+};
+
+__device__ __forceinline__ PassEntry pass_entry(const Params& P, const rtopk_row_trace* st, int p) {
+    PassEntry e;
+    if (p == 0) {
+        e.cand = (u32)P.n;
+        e.k_rem = (u32)P.k;
+        e.out_before = 0;
+        e.finished = false;
+        e.prev_multi = true;
+    } else {
+        e.cand = st->pass_rec[p - 1].cand_after;
+        e.k_rem = st->pass_rec[p - 1].k_after;
+        e.out_before = st->pass_rec[p - 1].out_before + st->pass_rec[p - 1].winners;
+        e.finished = e.cand == 0;
+        e.prev_multi = st->pass_rec[p - 1].where == 1u;
+    }
+    return e;
+}
+
+// What selectBin decides for one pass.
+struct Selection {
+    u32 bin;        // b: the bin holding the k-th key
+    u32 above;      // g: candidates in better bins -- certain winners
+    u32 inside;     // candidates in bin b
+    u32 k_inside;   // rank of the k-th key inside bin b
+    bool emit_all;  // inside == k_inside: the whole bin wins and the row is finished
+};
+
+// selectBin (Section 2.3.1) on suffix sums S held in LDS.  Contains barriers.
+template <int B>
+__device__ __forceinline__ Selection select_on_suffix_sums(const u32* S, int nb, u32 k_rem, u32* sel,
+                                                           rtopk_row_trace* st) {
+    Selection r;
+    r.bin = select_bin<B>(S, nb, k_rem, sel);
+    r.above = (r.bin + 1 < (u32)nb) ? S[r.bin + 1] : 0u;
+    r.inside = S[r.bin] - r.above;
+    r.k_inside = k_rem - r.above;
+    r.emit_all = r.inside == r.k_inside;
+    if (threadIdx.x == 0 && (k_rem == 0 || k_rem > S[0])) st->error |= 1u;  // inconsistent state: never expected
+    return r;
+}
+
+__device__ __forceinline__ void write_pass_record(rtopk_row_trace* st, int p, const PassInfo pi, const PassEntry& e,
+                                                  const Selection& sel, u32 where) {
+    // one thread; every field is written exactly once per call
+    st->pass_rec[p].bin = sel.bin;
+    st->pass_rec[p].k_after = sel.emit_all ? 0u : sel.k_inside;
+    st->pass_rec[p].cand_after = sel.emit_all ? 0u : sel.inside;
+    st->pass_rec[p].winners = sel.above + (sel.emit_all ? sel.inside : 0u);
+    st->pass_rec[p].out_before = e.out_before;
+    st->pass_rec[p].cand_before = e.cand;
+    st->pass_rec[p].window = pi.src | (pi.shift << 8) | (pi.bits << 16);
+    st->pass_rec[p].where = where;
+}
+
 // ------------------------------------------------------------------------------------------------
-// HIST phase
+// HIST phase: countBin (Section 3.1.1).  Leaves the suffix sums of the workgroup's histogram in LDS.
+// With many workgroups per row it also adds the histogram to the row's global one and stores the
+// suffix sums for the CLASSIFY sweep.
 // ------------------------------------------------------------------------------------------------
 template <class Source, int DT, int SRC, int B, bool SINGLE>
-__device__ __forceinline__ void hist_phase(Source& src, const Params& P, int p, int row, u32 wg, u32 G,
-                                           rtopk_row_trace* st, Shared<B>& sm, u32 where) {
+__device__ __forceinline__ void hist_phase(const Source& src, const Params& P, int p, int row, u32 wg, u32 G,
+                                           float a_s, Shared<B>& sm) {
     const PassInfo pi = P.pass[p];
     const int nb = 1 << pi.bits;
     const u32 tid = threadIdx.x;
-    const float a_s = st->a_s;
     const u32 ntiles = src.ntiles();
-    u32* ghist = P.ghist + (size_t)row * kMaxBins;
-    u32* swg_row = P.swg + (size_t)row * P.G * kSwgStride;
+    if (!SINGLE && wg >= ntiles) return;  // nothing to count; CLASSIFY ignores this workgroup's record
 
-    if (SINGLE || wg < ntiles) {
-        for (int j = tid; j < nb; j += B) sm.hist[j] = 0;
-        __syncthreads();
-        for (u32 tile = wg; tile < ntiles; tile += G) {
-            src.load(tile, tid);
+    for (int j = tid; j < nb; j += B) sm.hist[j] = 0;
+    __syncthreads();
+    typename Source::Tile cur, nxt;
+    if (wg < ntiles) src.load(wg, tid, cur);
+    for (u32 tile = wg; tile < ntiles; tile += G) {
+        const bool more = tile + G < ntiles;
+        if (more) src.load(tile + G, tid, nxt);  // next tile's loads fly while this one is counted
 #pragma unroll
-            for (int s = 0; s < Source::kSlots; ++s) {
-                u32 raw, idx;
-                bool valid;
-                src.get(s, raw, idx, valid);
-                if (valid) hist_add(sm.hist, digit_of<DT, SRC>(pi, raw, idx, P.dirmask, P.idx_max, a_s));
-            }
+        for (int s = 0; s < Source::kSlots; ++s) {
+            u32 raw, idx;
+            bool valid;
+            src.get(cur, s, raw, idx, valid);
+            if (valid) hist_add(sm.hist, digit_of<DT, SRC>(pi, raw, idx, P.dirmask, P.idx_max, a_s));
         }
-        __syncthreads();
-        if (!SINGLE) {
-            for (int j = tid; j < nb; j += B) {
-                u32 c = sm.hist[j];
-                if (c) atomicAdd(&ghist[j], c);
-            }
-        }
-        suffix_sums_in_place<B>(sm.hist, nb, sm.wsum);
-        if (!SINGLE) {
-            u32* mine = swg_row + (size_t)wg * kSwgStride;
-            for (int j = tid; j < nb; j += B) mine[j] = sm.hist[j];
-            if (tid == 0) mine[nb] = 0;
-        }
+        if (more) cur = nxt;
     }
+    __syncthreads();
     if (!SINGLE) {
-        // publish, then find out whether this workgroup is the row's last one
-        __threadfence();
-        __syncthreads();
-        if (tid == 0) sm.flag = (atomicAdd(&st->ticket, 1u) == G - 1) ? 1u : 0u;
-        __syncthreads();
-        if (!sm.flag) return;
-        __threadfence();
+        u32* ghist = P.ghist + ((size_t)(p & 1) * P.batch + row) * kMaxBins;
         for (int j = tid; j < nb; j += B) {
-            sm.hist[j] = ghist[j];
-            ghist[j] = 0;  // ready for the next pass
+            u32 c = sm.hist[j];
+            if (c) atomicAdd(&ghist[j], c);
         }
-        __syncthreads();
-        suffix_sums_in_place<B>(sm.hist, nb, sm.wsum);
     }
-
-    // selectBin on the row's suffix sums
-    const u32 k_rem = st->k_rem;
-    const u32 out_count = st->out_count;
-    const u32 b = select_bin<B>(sm.hist, nb, k_rem, &sm.sel);
-    const u32 g = (b + 1 < (u32)nb) ? sm.hist[b + 1] : 0u;  // candidates in better bins: certain winners
-    const u32 cp = sm.hist[b] - g;                          // candidates inside the chosen bin
-    const u32 kp = k_rem - g;                               // rank of the k-th key inside the bin
-    const bool emit_all = (cp == kp);                       // the whole bin wins: selection is complete
-    const bool bad = (k_rem == 0) || (k_rem > sm.hist[0]);  // inconsistent state: never expected
-
+    suffix_sums_in_place<B>(sm.hist, nb, sm.wsum);
     if (!SINGLE) {
-        // exact write offsets for every workgroup of the CLASSIFY sweep
-        const u32 active = ntiles < G ? ntiles : G;
-        u32* bases = P.bases + (size_t)row * P.G * 2;
-        if (tid == 0) { sm.carry[0] = 0; sm.carry[1] = 0; }
-        __syncthreads();
-        for (u32 w0 = 0; w0 < active; w0 += B) {
-            const u32 w = w0 + tid;
-            u32 W = 0, C = 0;
-            if (w < active) {
-                const u32* rec = swg_row + (size_t)w * kSwgStride;
-                const u32 sb = rec[b], sb1 = rec[b + 1];
-                C = sb - sb1;
-                W = sb1;
-                if (emit_all) { W += C; C = 0; }
-            }
-            const u32 cw = sm.carry[0], cc = sm.carry[1];
-            const u32 iw = block_inclusive_scan<B>(W, sm.wsum);
-            const u32 ic = block_inclusive_scan<B>(C, sm.wsum);
-            if (w < active) {
-                bases[2 * w] = out_count + cw + iw - W;
-                bases[2 * w + 1] = cc + ic - C;
-            }
-            __syncthreads();
-            if (tid == B - 1) { sm.carry[0] = cw + iw; sm.carry[1] = cc + ic; }
-            __syncthreads();
-        }
-    }
-    if (tid == 0) {
-        st->bin = b;
-        st->emit_all = emit_all ? 1u : 0u;
-        st->win_total = g + (emit_all ? cp : 0u);
-        st->next_count = emit_all ? 0u : cp;
-        st->k_rem = kp;
-        st->ticket = 0;
-        if (bad) st->error |= 1u;
-        if (p < kMaxPasses) {
-            st->pass_rec[p].bin = b;
-            st->pass_rec[p].k_after = emit_all ? 0u : kp;
-            st->pass_rec[p].cand_after = emit_all ? 0u : cp;
-            st->pass_rec[p].winners = g + (emit_all ? cp : 0u);
-            st->pass_rec[p].source = pi.src;
-            st->pass_rec[p].shift = pi.shift;
-            st->pass_rec[p].bits = pi.bits;
-            st->pass_rec[p].where = where;
-        }
-        st->passes_run = (u32)p + 1u;
+        u32* mine = P.swg + ((size_t)row * P.G + wg) * kSwgStride;
+        for (int j = tid; j < nb; j += B) mine[j] = sm.hist[j];
+        if (tid == 0) mine[nb] = 0;
     }
 }
 
 // ------------------------------------------------------------------------------------------------
-// CLASSIFY phase
+// CLASSIFY phase: selectBin, then selectCandidate fused with the filter.
 // ------------------------------------------------------------------------------------------------
 template <int DT>
 __device__ __forceinline__ void store_value(void* out_row, u32 pos, u32 raw) {
@@ -172,42 +163,70 @@ __device__ __forceinline__ void store_value(void* out_row, u32 pos, u32 raw) {
 }
 
 template <class Source, int DT, int SRC, int B, bool SINGLE>
-__device__ __forceinline__ void classify_phase(Source& src, const Params& P, int p, int row, u32 wg, u32 G,
-                                               rtopk_row_trace* st, Shared<B>& sm) {
+__device__ __forceinline__ void classify_phase(const Source& src, const Params& P, int p, int row, u32 wg, u32 G,
+                                               const PassEntry& e, rtopk_row_trace* st, Shared<B>& sm, u32 where) {
     const PassInfo pi = P.pass[p];
+    const int nb = 1 << pi.bits;
     const u32 tid = threadIdx.x;
     const u32 lane = lane_id();
     const u32 wave = tid >> 6;
     constexpr int NW = B / 64;
     const float a_s = st->a_s;
-    const u32 b = st->bin;
-    const bool emit_all = st->emit_all != 0;
     const u32 ntiles = src.ntiles();
     const u32 kk = (u32)P.k;
     const u32 ncap = (u32)P.n;
 
+    typename Source::Tile cur, nxt;
+    if (wg < ntiles) src.load(wg, tid, cur);  // first tile's loads fly during the selection below
+
+    u32 runW = e.out_before, runC = 0;
+    if (!SINGLE) {
+        // every workgroup repeats selectBin on the row's global histogram (cheap, and it spares a
+        // grid-wide hand-off), then sums the counts of the workgroups before it
+        const u32* ghist = P.ghist + ((size_t)(p & 1) * P.batch + row) * kMaxBins;
+        for (int j = tid; j < nb; j += B) sm.hist[j] = ghist[j];
+        __syncthreads();
+        suffix_sums_in_place<B>(sm.hist, nb, sm.wsum);
+    }
+    const Selection sel = select_on_suffix_sums<B>(sm.hist, nb, e.k_rem, &sm.sel, st);
+    if (!SINGLE) {
+        const u32 active = ntiles < G ? ntiles : G;
+        const u32 upto = wg < active ? wg : active;
+        const u32* swg_row = P.swg + (size_t)row * P.G * kSwgStride;
+        u32 W = 0, C = 0;
+        for (u32 w = tid; w < upto; w += B) {
+            const u32* rec = swg_row + (size_t)w * kSwgStride;
+            const u32 sb = rec[sel.bin], sb1 = rec[sel.bin + 1];
+            W += sel.emit_all ? sb : sb1;
+            C += sel.emit_all ? 0u : sb - sb1;
+        }
+        block_sum2<B>(W, C, sm.red);
+        runW += W;
+        runC = C;
+        if (wg == 0) {
+            // the next pass accumulates into the other histogram buffer: clear it now
+            u32* other = P.ghist + ((size_t)((p + 1) & 1) * P.batch + row) * kMaxBins;
+            for (int j = tid; j < kMaxBins; j += B) other[j] = 0;
+        }
+    }
+    if (wg == 0 && tid == 0) write_pass_record(st, p, pi, e, sel, where);
+
     void* out_v = (char*)P.out_values + (size_t)row * (size_t)P.k * KeyOf<DT>::kBytes;
     long long* out_i = P.out_indices + (size_t)row * (size_t)P.k;
     uint2* cand_out = P.cand[p & 1] + (size_t)row * (size_t)P.n;
+    const u32 b = sel.bin;
+    const bool emit_all = sel.emit_all;
 
-    u32 runW, runC;
-    if (SINGLE) {
-        runW = st->out_count;
-        runC = 0;
-    } else {
-        const u32* bases = P.bases + (size_t)row * P.G * 2;
-        runW = (wg < ntiles) ? bases[2 * wg] : 0u;
-        runC = (wg < ntiles) ? bases[2 * wg + 1] : 0u;
-    }
     u32 parity = 0;
     for (u32 tile = wg; tile < ntiles; tile += G) {
-        src.load(tile, tid);
+        const bool more = tile + G < ntiles;
+        if (more) src.load(tile + G, tid, nxt);
         u32 winbits = 0, candbits = 0, totW = 0, totC = 0;
 #pragma unroll
         for (int s = 0; s < Source::kSlots; ++s) {
             u32 raw, idx;
             bool valid;
-            src.get(s, raw, idx, valid);
+            src.get(cur, s, raw, idx, valid);
             const u32 dg = digit_of<DT, SRC>(pi, raw, idx, P.dirmask, P.idx_max, a_s);
             const bool eq = valid && dg == b;
             const bool w = valid && (dg > b || (emit_all && eq));
@@ -231,7 +250,7 @@ __device__ __forceinline__ void classify_phase(Source& src, const Params& P, int
             allC += cc;
         }
         u32 posW = runW + preW, posC = runC + preC;
-        if (allW | allC) {
+        if (totW | totC) {
 #pragma unroll
             for (int s = 0; s < Source::kSlots; ++s) {
                 const bool w = (winbits >> s) & 1u;
@@ -241,7 +260,7 @@ __device__ __forceinline__ void classify_phase(Source& src, const Params& P, int
                 if (mw | mc) {
                     u32 raw, idx;
                     bool valid;
-                    src.get(s, raw, idx, valid);
+                    src.get(cur, s, raw, idx, valid);
                     if (w) {
                         const u32 pos = posW + mbcnt64(mw);
                         if (pos < kk) {
@@ -261,33 +280,8 @@ __device__ __forceinline__ void classify_phase(Source& src, const Params& P, int
         runW += allW;
         runC += allC;
         parity ^= 1u;
+        if (more) cur = nxt;
     }
-
-    // the row's last workgroup moves the loop state on (Algorithm 1: next digit)
-    bool last = true;
-    if (!SINGLE) {
-        __threadfence();
-        __syncthreads();
-        if (tid == 0) sm.flag = (atomicAdd(&st->ticket, 1u) == G - 1) ? 1u : 0u;
-        __syncthreads();
-        last = sm.flag != 0;
-    } else {
-        __syncthreads();
-    }
-    if (last && tid == 0) {
-        const u32 next = st->next_count;
-        st->out_count += st->win_total;
-        st->cand_count = next;
-        st->pass = (u32)p + 1u;
-        st->ticket = 0;
-        if (emit_all || next == 0) {
-            st->done = 1;
-        } else if (p + 1 >= P.npass) {
-            st->done = 1;
-            st->error |= 2u;  // digits exhausted with candidates left: impossible for unique extended keys
-        }
-    }
-    if (SINGLE) __syncthreads();
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -305,8 +299,6 @@ __device__ __forceinline__ void init_row(const Params& P, int row, rtopk_row_tra
     // called by one thread
     u32* w = (u32*)st;
     for (int i = 0; i < (int)(sizeof(rtopk_row_trace) / 4); ++i) w[i] = 0;
-    st->k_rem = (u32)P.k;
-    st->cand_count = (u32)P.n;
     float a_s = 0.0f;
     if (DT == RTOPK_F32 && (P.flags & RTOPK_FLAG_SCALING)) {
         const u64 j = mix64(P.seed + 0x9E3779B97F4A7C15ull * (u64)(row + 1)) % (u64)P.n;
@@ -319,29 +311,32 @@ __device__ __forceinline__ void init_row(const Params& P, int row, rtopk_row_tra
 template <int DT>
 __global__ void __launch_bounds__(256) k_init(Params P) {
     const int row = blockIdx.x;
-    u32* ghist = P.ghist + (size_t)row * kMaxBins;
-    for (int j = threadIdx.x; j < kMaxBins; j += 256) ghist[j] = 0;
+    for (int h = 0; h < 2; ++h) {
+        u32* ghist = P.ghist + ((size_t)h * P.batch + row) * kMaxBins;
+        for (int j = threadIdx.x; j < kMaxBins; j += 256) ghist[j] = 0;
+    }
     if (threadIdx.x == 0) init_row<DT>(P, row, row_state(P, row));
 }
 
 // ------------------------------------------------------------------------------------------------
 // many workgroups per row: one launch per phase per pass, covering every row (task rescheduling,
-// Section 3.2.1: pass i of all tasks runs together; grid = workgroups-per-row x rows)
+// Section 3.2.1: pass i of all tasks runs together; grid = workgroups-per-row x rows).
+// A pass runs here if the previous one did and left more than `small` candidates; every workgroup
+// evaluates that on records no kernel of the same pass writes, so all of them agree.
 // ------------------------------------------------------------------------------------------------
-__device__ __forceinline__ bool row_skips_pass(const Params& P, const rtopk_row_trace* st, int p) {
-    if (st->done || st->pass != (u32)p) return true;
-    return p > 0 && st->cand_count <= P.small;  // few candidates left: the finish kernel takes over
+__device__ __forceinline__ bool multi_runs_pass(const Params& P, const PassEntry& e, int p) {
+    if (p == 0) return true;
+    return e.prev_multi && !e.finished && e.cand > P.small;
 }
 
 template <int DT, int SRC>
 __global__ void __launch_bounds__(kGridBlock) k_hist_keys(Params P) {
     __shared__ Shared<kGridBlock> sm;
     const int row = blockIdx.y;
-    rtopk_row_trace* st = row_state(P, row);
-    if (row_skips_pass(P, st, 0)) return;
+    const rtopk_row_trace* st = row_state(P, row);
     KeySource<DT, kGridBlock, kVecs> src;
     src.init(P.keys, P.n, row);
-    hist_phase<decltype(src), DT, SRC, kGridBlock, false>(src, P, 0, row, blockIdx.x, gridDim.x, st, sm, 1u);
+    hist_phase<decltype(src), DT, SRC, kGridBlock, false>(src, P, 0, row, blockIdx.x, gridDim.x, st->a_s, sm);
 }
 
 template <int DT, int SRC>
@@ -349,21 +344,22 @@ __global__ void __launch_bounds__(kGridBlock) k_classify_keys(Params P) {
     __shared__ Shared<kGridBlock> sm;
     const int row = blockIdx.y;
     rtopk_row_trace* st = row_state(P, row);
-    if (row_skips_pass(P, st, 0)) return;
+    const PassEntry e = pass_entry(P, st, 0);
     KeySource<DT, kGridBlock, kVecs> src;
     src.init(P.keys, P.n, row);
-    classify_phase<decltype(src), DT, SRC, kGridBlock, false>(src, P, 0, row, blockIdx.x, gridDim.x, st, sm);
+    classify_phase<decltype(src), DT, SRC, kGridBlock, false>(src, P, 0, row, blockIdx.x, gridDim.x, e, st, sm, 1u);
 }
 
 template <int DT>
 __global__ void __launch_bounds__(kGridBlock) k_hist_cand(Params P, int p) {
     __shared__ Shared<kGridBlock> sm;
     const int row = blockIdx.y;
-    rtopk_row_trace* st = row_state(P, row);
-    if (row_skips_pass(P, st, p)) return;
+    const rtopk_row_trace* st = row_state(P, row);
+    const PassEntry e = pass_entry(P, st, p);
+    if (!multi_runs_pass(P, e, p)) return;
     CandSource<kGridBlock, kVecs> src;
-    src.init(P.cand[(p - 1) & 1] + (size_t)row * (size_t)P.n, st->cand_count);
-    hist_phase<decltype(src), DT, SRC_RUNTIME, kGridBlock, false>(src, P, p, row, blockIdx.x, gridDim.x, st, sm, 1u);
+    src.init(P.cand[(p - 1) & 1] + (size_t)row * (size_t)P.n, e.cand);
+    hist_phase<decltype(src), DT, SRC_RUNTIME, kGridBlock, false>(src, P, p, row, blockIdx.x, gridDim.x, st->a_s, sm);
 }
 
 template <int DT>
@@ -371,31 +367,33 @@ __global__ void __launch_bounds__(kGridBlock) k_classify_cand(Params P, int p) {
     __shared__ Shared<kGridBlock> sm;
     const int row = blockIdx.y;
     rtopk_row_trace* st = row_state(P, row);
-    if (row_skips_pass(P, st, p)) return;
+    const PassEntry e = pass_entry(P, st, p);
+    if (!multi_runs_pass(P, e, p)) return;
     CandSource<kGridBlock, kVecs> src;
-    src.init(P.cand[(p - 1) & 1] + (size_t)row * (size_t)P.n, st->cand_count);
-    classify_phase<decltype(src), DT, SRC_RUNTIME, kGridBlock, false>(src, P, p, row, blockIdx.x, gridDim.x, st, sm);
+    src.init(P.cand[(p - 1) & 1] + (size_t)row * (size_t)P.n, e.cand);
+    classify_phase<decltype(src), DT, SRC_RUNTIME, kGridBlock, false>(src, P, p, row, blockIdx.x, gridDim.x, e, st, sm, 1u);
 }
 
 // ------------------------------------------------------------------------------------------------
 // one workgroup per row
 // ------------------------------------------------------------------------------------------------
 
-// Remaining passes of one row on its candidate arrays, by a single workgroup.
+// Remaining passes of one row on its candidate arrays, by a single workgroup, starting at pass p.
 template <int DT>
 __device__ __forceinline__ void finish_row(const Params& P, int row, rtopk_row_trace* st, Shared<kRowBlock>& sm,
-                                           u32 where) {
-    for (;;) {
-        // state is rewritten by thread 0 at the end of each phase, behind a barrier
-        if (st->done) break;
-        const int p = (int)st->pass;
-        if (p >= P.npass) break;
+                                           int p, u32 where) {
+    for (; p < P.npass; ++p) {
+        __syncthreads();  // the previous pass's record and candidates are visible to the whole workgroup
+        const PassEntry e = pass_entry(P, st, p);
+        if (e.finished) return;
         CandSource<kRowBlock, kVecs> src;
-        src.init(P.cand[(p - 1) & 1] + (size_t)row * (size_t)P.n, st->cand_count);
-        hist_phase<decltype(src), DT, SRC_RUNTIME, kRowBlock, true>(src, P, p, row, 0u, 1u, st, sm, where);
-        __syncthreads();
-        classify_phase<decltype(src), DT, SRC_RUNTIME, kRowBlock, true>(src, P, p, row, 0u, 1u, st, sm);
+        src.init(P.cand[(p - 1) & 1] + (size_t)row * (size_t)P.n, e.cand);
+        hist_phase<decltype(src), DT, SRC_RUNTIME, kRowBlock, true>(src, P, p, row, 0u, 1u, st->a_s, sm);
+        classify_phase<decltype(src), DT, SRC_RUNTIME, kRowBlock, true>(src, P, p, row, 0u, 1u, e, st, sm, where);
     }
+    __syncthreads();
+    // digits exhausted: extended keys are unique, so the last pass must have taken its whole bin
+    if (threadIdx.x == 0 && P.npass > 0 && st->pass_rec[P.npass - 1].cand_after != 0) st->error |= 2u;
 }
 
 template <int DT>
@@ -403,7 +401,9 @@ __global__ void __launch_bounds__(kRowBlock) k_finish(Params P) {
     __shared__ Shared<kRowBlock> sm;
     const int row = blockIdx.x;
     rtopk_row_trace* st = row_state(P, row);
-    finish_row<DT>(P, row, st, sm, 2u);
+    int p = 0;
+    while (p < P.npass && st->pass_rec[p].where != 0u) ++p;  // first pass the grid kernels left undone
+    finish_row<DT>(P, row, st, sm, p, 2u);
 }
 
 // Whole selection of one row in one kernel (many short rows: no global atomics, no extra launches).
@@ -415,13 +415,13 @@ __global__ void __launch_bounds__(kRowBlock) k_row(Params P) {
     if (threadIdx.x == 0) init_row<DT>(P, row, st);
     __syncthreads();
     {
+        const PassEntry e = pass_entry(P, st, 0);
         KeySource<DT, kRowBlock, kVecs> src;
         src.init(P.keys, P.n, row);
-        hist_phase<decltype(src), DT, SRC, kRowBlock, true>(src, P, 0, row, 0u, 1u, st, sm, 3u);
-        __syncthreads();
-        classify_phase<decltype(src), DT, SRC, kRowBlock, true>(src, P, 0, row, 0u, 1u, st, sm);
+        hist_phase<decltype(src), DT, SRC, kRowBlock, true>(src, P, 0, row, 0u, 1u, st->a_s, sm);
+        classify_phase<decltype(src), DT, SRC, kRowBlock, true>(src, P, 0, row, 0u, 1u, e, st, sm, 3u);
     }
-    finish_row<DT>(P, row, st, sm, 3u);
+    finish_row<DT>(P, row, st, sm, 1, 3u);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -521,7 +521,7 @@ static Layout make_layout(int64_t batch, int64_t n, const Config& c) {
     L.state_off = off;
     off = align_up(off + (size_t)batch * RTOPK_TRACE_STRIDE, 256);
     L.ghist_off = off;
-    off = align_up(off + (size_t)batch * kMaxBins * 4, 256);
+    off = align_up(off + (size_t)2 * batch * kMaxBins * 4, 256);
     L.bases_off = off;
     off = align_up(off + (size_t)batch * c.G * 2 * 4, 256);
     L.swg_off = off;
