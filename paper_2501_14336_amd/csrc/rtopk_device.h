@@ -17,6 +17,8 @@ constexpr int kSwgStride = kMaxBins + 8;  // per-workgroup suffix-sum record: r 
 constexpr int kMaxPasses = RTOPK_TRACE_MAX_PASSES;
 
 enum { SRC_SCALED = 0, SRC_KEY = 1, SRC_IDX = 2, SRC_RUNTIME = -1 };
+constexpr u32 kInternalStream = 1u << 31;  // Params::flags: the input is much larger than the last-level cache
+constexpr int kStageCap = 256;             // entries per wave in each LDS write buffer (Section 3.1.2)
 
 // One digit pass: bits [shift, shift + bits) of the 32-bit ordered key of `src`.
 struct PassInfo {
@@ -39,7 +41,7 @@ struct Params {
     u32 idx_max;             // 2^ceil(log2 n) - 1: the index digit source is idx_max - index
     u32 small;               // candidate count at or below which one workgroup finishes the row
     int npass;
-    u32 flags;
+    u32 flags;               // RTOPK_FLAG_* | kInternalStream
     u64 seed;
     PassInfo pass[kMaxPasses];
 };
@@ -117,22 +119,60 @@ __device__ __forceinline__ u32 digit_of(const PassInfo pi, u32 raw, u32 idx, u32
     return (u >> pi.shift) & ((1u << pi.bits) - 1u);
 }
 
+// Everything a kernel needs to turn elements into digits of one pass, as wave-uniform scalars.
+// The last four fields drive the branch-free key of the first pass over X:
+//   key = b ^ (((b >>arith 31) ^ xd) & am | om), NaN -> nanv
+// which is the ordered key for "largest" (xd 0, am ~0, om sign bit) and its complement for
+// "smallest" (xd ~0, am ~sign bit, om 0), without a separate direction step.
+struct DigitCtx {
+    PassInfo pi;
+    u32 dirmask, idx_max;
+    float a_s;
+    u32 xd, am, om, nanv;
+};
+
+__device__ __forceinline__ DigitCtx make_digit_ctx(const Params& P, int p, float a_s) {
+    DigitCtx c;
+    c.pi = P.pass[p];
+    c.dirmask = P.dirmask;
+    c.idx_max = P.idx_max;
+    c.a_s = a_s;
+    const bool largest = P.dirmask == 0;
+    c.xd = largest ? 0u : 0xffffffffu;
+    c.am = largest ? 0xffffffffu : 0x7fffffffu;
+    c.om = largest ? 0x80000000u : 0u;
+    c.nanv = largest ? 0xffffffffu : 0u;
+    return c;
+}
+
 // ------------------------------------------------------------------------------------------------
 // tile sources.  A tile is B*V 16-byte vectors; lane t of the workgroup owns vectors t, t+B, ...
 // so that every load instruction of a wave covers 1 KiB of consecutive addresses.
 // ------------------------------------------------------------------------------------------------
 
+typedef u32 u32x4 __attribute__((ext_vector_type(4)));
+typedef const __attribute__((address_space(1))) u32x4* global_vec_ptr;
+// 16-byte load from global memory (explicitly global, so that it counts on the vector-memory
+// counter only and never waits for LDS traffic).  NT: the data is far larger than the last-level
+// cache and is streamed with non-temporal loads so that it does not displace what is reused.
+template <bool NT>
+__device__ __forceinline__ uint4 load16(const uint4* p) {
+    const global_vec_ptr g = (global_vec_ptr)p;
+    const u32x4 v = NT ? __builtin_nontemporal_load(g) : *g;
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 // Registers of one lane's share of a tile.
 template <int V>
 struct TileRegs {
     uint4 r[V];
-    u32 e0[V];  // index of element 0 of each vector (row index for X, position for candidates)
-    bool full;  // every element of the tile is valid
+    u32 tile;   // tile number (wave-uniform)
+    bool full;  // every element of the tile is valid (wave-uniform)
 };
 
 // The input row X.  Loads start at the 16-byte aligned address at or before the row's first element
 // and elements outside [0, n) are masked (on-demand offset padding, Section 3.2.2).
-template <int DT, int B, int V>
+template <int DT, int B, int V, bool NT>
 struct KeySource {
     static constexpr int kElemBytes = KeyOf<DT>::kBytes;
     static constexpr int E = 16 / kElemBytes;  // elements per vector
@@ -154,23 +194,90 @@ struct KeySource {
         nvec = ((u64)lead + (u64)n + E - 1) / E;
     }
     __device__ __forceinline__ u32 ntiles() const { return (u32)((nvec + kTileVecs - 1) / kTileVecs); }
+    // tiles [f0, f1) contain only elements of the row
+    __device__ __forceinline__ void full_range(u32& f0, u32& f1) const {
+        f0 = lead != 0 ? 1u : 0u;
+        f1 = (u32)(((u64)lead + (u64)n) / ((u64)kTileVecs * E));
+        if (f1 < f0) f1 = f0;
+    }
+    __device__ __forceinline__ void load_full(u32 tile, u32 tid, Tile& t) const {
+        const u64 v0 = (u64)tile * kTileVecs;
+        t.tile = tile;
+        t.full = true;
+#pragma unroll
+        for (int u = 0; u < V; ++u) t.r[u] = load16<NT>(abase + (v0 + (u64)u * B + tid));
+    }
     __device__ __forceinline__ void load(u32 tile, u32 tid, Tile& t) const {
         u64 v0 = (u64)tile * kTileVecs;
+        t.tile = tile;
         t.full = (tile != 0 || lead == 0) && ((v0 + kTileVecs) * E <= (u64)lead + (u64)n);
 #pragma unroll
         for (int u = 0; u < V; ++u) {
             u64 v = v0 + (u64)u * B + tid;
-            t.e0[u] = (u32)(v * E) - lead;
             if (t.full || v < nvec)
-                t.r[u] = abase[v];
+                t.r[u] = load16<NT>(abase + v);
             else
                 t.r[u] = make_uint4(0, 0, 0, 0);
         }
     }
+    // Digits of the E elements of vector u for the FIRST pass, whose digit is the key's top bits
+    // (pi.shift + pi.bits == 32).  SRC is SRC_KEY or, fp32 only, SRC_SCALED.
+    template <int SRC>
+    __device__ __forceinline__ void digits(const Tile& t, int u, const DigitCtx& c, u32 (&dg)[E]) const {
+        const uint4 q = t.r[u];
+        const u32 w[4] = {q.x, q.y, q.z, q.w};
+        if (E == 4) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                u32 b = w[j];
+                if (SRC == SRC_SCALED) b = __float_as_uint(__uint_as_float(b) - c.a_s);
+                const u32 sgn = (u32)((int32_t)b >> 31);
+                u32 key = b ^ (((sgn ^ c.xd) & c.am) | c.om);
+                const float f = __uint_as_float(b);
+                key = (f != f) ? c.nanv : key;
+                dg[j] = key >> c.pi.shift;
+            }
+        } else {
+            // two 16-bit keys per word, transformed together
+            const u32 thr = (DT == RTOPK_F16) ? 0x03ff03ffu : 0x007f007fu;  // 0x7fff - (largest non-NaN magnitude)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const u32 x = w[j];
+                const u32 sb = x & 0x80008000u;
+                u32 key = x ^ ((sb - (sb >> 15)) | 0x80008000u);          // negatives: all bits, others: sign bit
+                const u32 nb = ((x & 0x7fff7fffu) + thr) & 0x80008000u;  // bit 15 of a half set iff it is NaN
+                key |= (nb - (nb >> 15)) | nb;                            // NaN halves -> 0xffff
+                key ^= c.xd;                                               // "smallest": complement
+                dg[2 * j] = (key & 0xffffu) >> (c.pi.shift - 16);
+                dg[2 * j + 1] = key >> c.pi.shift;
+            }
+        }
+    }
+    // Element s of the tile as an fp32 number that orders like the element (exact widening for
+    // 16-bit types; x - a_s under scaling).  NaN stays NaN.
+    template <int SRC>
+    __device__ __forceinline__ float value(const Tile& t, int s, float a_s) const {
+        const int u = s / E, j = s % E;
+        const uint4 q = t.r[u];
+        if (E == 4) {
+            const float f = __uint_as_float(j == 0 ? q.x : j == 1 ? q.y : j == 2 ? q.z : q.w);
+            return SRC == SRC_SCALED ? f - a_s : f;
+        } else {
+            const int w = j >> 1;
+            const u32 word = w == 0 ? q.x : w == 1 ? q.y : w == 2 ? q.z : q.w;
+            if (DT == RTOPK_BF16) {
+                return __uint_as_float((j & 1) ? (word & 0xffff0000u) : (word << 16));
+            } else {
+                const uint16_t h = (uint16_t)((j & 1) ? (word >> 16) : word);
+                return (float)__builtin_bit_cast(_Float16, h);
+            }
+        }
+    }
     __device__ __forceinline__ void get(const Tile& t, int s, u32& raw, u32& idx, bool& valid) const {
         const int u = s / E, j = s % E;
-        idx = t.e0[u] + j;
-        valid = t.full || idx < n;  // the lead-in wraps to huge values, vectors past the end start at >= n
+        // row index of the element; the lead-in wraps to huge values, vectors past the end start at >= n
+        idx = (t.tile * (u32)kTileVecs + (u32)(u * B) + threadIdx.x) * (u32)E + (u32)j - lead;
+        valid = t.full || idx < n;
         const uint4 q = t.r[u];
         if (E == 4) {
             raw = j == 0 ? q.x : j == 1 ? q.y : j == 2 ? q.z : q.w;
@@ -200,26 +307,115 @@ struct CandSource {
         nvec = ((u64)count_ + 1) / 2;
     }
     __device__ __forceinline__ u32 ntiles() const { return (u32)((nvec + kTileVecs - 1) / kTileVecs); }
+    __device__ __forceinline__ void full_range(u32& f0, u32& f1) const {
+        f0 = 0;
+        f1 = (u32)((u64)count / ((u64)kTileVecs * E));
+    }
+    __device__ __forceinline__ void load_full(u32 tile, u32 tid, Tile& t) const {
+        const u64 v0 = (u64)tile * kTileVecs;
+        t.tile = tile;
+        t.full = true;
+#pragma unroll
+        for (int u = 0; u < V; ++u) t.r[u] = load16<false>(base + (v0 + (u64)u * B + tid));
+    }
     __device__ __forceinline__ void load(u32 tile, u32 tid, Tile& t) const {
         u64 v0 = (u64)tile * kTileVecs;
+        t.tile = tile;
         t.full = (v0 + kTileVecs) * E <= (u64)count;
 #pragma unroll
         for (int u = 0; u < V; ++u) {
             u64 v = v0 + (u64)u * B + tid;
-            t.e0[u] = (u32)(v * E);
             if (t.full || v < nvec)
-                t.r[u] = base[v];
+                t.r[u] = load16<false>(base + v);
             else
                 t.r[u] = make_uint4(0, 0, 0, 0);
         }
     }
+    // Digits of the two elements of vector u for any pass (source chosen at run time).
+    template <int DT>
+    __device__ __forceinline__ void digits(const Tile& t, int u, const DigitCtx& c, u32 (&dg)[E]) const {
+        dg[0] = digit_of<DT, SRC_RUNTIME>(c.pi, t.r[u].x, t.r[u].y, c.dirmask, c.idx_max, c.a_s);
+        dg[1] = digit_of<DT, SRC_RUNTIME>(c.pi, t.r[u].z, t.r[u].w, c.dirmask, c.idx_max, c.a_s);
+    }
     __device__ __forceinline__ void get(const Tile& t, int s, u32& raw, u32& idx, bool& valid) const {
         const int u = s / E, j = s % E;
-        valid = t.full || (t.e0[u] + j) < count;
+        valid = t.full || ((t.tile * (u32)kTileVecs + (u32)(u * B) + threadIdx.x) * (u32)E + (u32)j) < count;
         raw = j ? t.r[u].z : t.r[u].x;
         idx = j ? t.r[u].w : t.r[u].y;
     }
 };
+
+// Visit the tiles wg, wg + G, wg + 2G, ... of a source.
+//
+// Tiles that lie entirely inside the data (all but possibly the first and the last of a row) go through a
+// software pipeline of DEPTH tiles: DEPTH + 1 register sets take turns, the loads of the next DEPTH tiles
+// are in flight while one is processed, every load in the steady state is unconditional and no register
+// set is ever copied, so the compiler can wait for exactly the oldest set instead of draining the queue.
+// The at most two partial tiles are handled afterwards, unpipelined.  f(tile) is called once per tile.
+template <int DEPTH, class Source, class F>
+__device__ __forceinline__ void for_each_tile(const Source& src, u32 wg, u32 G, u32 ntiles, F&& f) {
+    const u32 tid = threadIdx.x;
+    u32 f0, f1;  // tiles [f0, f1) are full
+    src.full_range(f0, f1);
+    // my first full tile and how many I own
+    u32 first = wg;
+    if (first < f0) first += ((f0 - first + G - 1) / G) * G;
+    const u32 m = first < f1 ? (f1 - first + G - 1) / G : 0u;
+    if (m != 0) {
+        if constexpr (DEPTH == 2) {
+            typename Source::Tile a, b, c;
+            src.load_full(first, tid, a);
+            if (m > 1) src.load_full(first + G, tid, b);
+            u32 i = 0;
+            for (;;) {
+                if (i + 2 >= m) { f(a); if (i + 1 < m) f(b); break; }
+                src.load_full(first + (i + 2) * G, tid, c);
+                f(a);
+                ++i;
+                if (i + 2 >= m) { f(b); if (i + 1 < m) f(c); break; }
+                src.load_full(first + (i + 2) * G, tid, a);
+                f(b);
+                ++i;
+                if (i + 2 >= m) { f(c); if (i + 1 < m) f(a); break; }
+                src.load_full(first + (i + 2) * G, tid, b);
+                f(c);
+                ++i;
+            }
+        } else if constexpr (DEPTH == 1) {
+            typename Source::Tile a, b;
+            src.load_full(first, tid, a);
+            u32 i = 0;
+            for (;;) {
+                if (i + 1 >= m) { f(a); break; }
+                src.load_full(first + (i + 1) * G, tid, b);
+                f(a);
+                ++i;
+                if (i + 1 >= m) { f(b); break; }
+                src.load_full(first + (i + 1) * G, tid, a);
+                f(b);
+                ++i;
+            }
+        } else {
+            for (u32 i = 0; i < m; ++i) {
+                typename Source::Tile a;
+                src.load_full(first + i * G, tid, a);
+                f(a);
+            }
+        }
+    }
+    // partial tiles: those of mine outside [f0, f1)
+    for (u32 t = wg; t < ntiles; t += G) {
+        if (t >= f0 && t < f1) {
+            // skip the full range in one step
+            const u32 skip = (f1 - t + G - 1) / G;
+            t += (skip - 1) * G;
+            continue;
+        }
+        typename Source::Tile e;
+        src.load(t, tid, e);
+        f(e);
+    }
+}
 
 // ------------------------------------------------------------------------------------------------
 // workgroup-wide scans
@@ -303,12 +499,14 @@ __device__ __forceinline__ u32 select_bin(const u32* S, int nb, u32 k, u32* sel)
 // Lanes holding the same digit as the wave's first active lane are merged into one LDS atomic
 // (register-level aggregation, the "warp" level of the paper's Table 1); everything else goes
 // straight to the LDS atomic (the "block" level).  Called by the lanes that hold a valid element.
-__device__ __forceinline__ void hist_add(u32* h, u32 dg) {
+__device__ __forceinline__ void hist_add_plain(u32* h, u32 dg) { atomicAdd(&h[dg], 1u); }
+
+__device__ __forceinline__ void hist_add(u32* h, u32 dg, u32 lane) {
     const u32 d0 = __builtin_amdgcn_readfirstlane(dg);
     const bool same = dg == d0;
     const u64 m = ballot64(same);
     const u32 cnt = (u32)__popcll(m);
-    const bool leader = mbcnt64(m) == 0;  // lowest lane of the merged group
+    const bool leader = lane == (u32)__builtin_ctzll(m);  // lowest lane of the merged group
     if (!same || leader) atomicAdd(&h[dg], same ? cnt : 1u);
 }
 

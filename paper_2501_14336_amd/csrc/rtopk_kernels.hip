@@ -29,17 +29,38 @@
 
 namespace rtopk {
 
-constexpr int kGridBlock = 512;   // threads per workgroup, many-workgroups-per-row kernels
-constexpr int kRowBlock = 1024;   // threads per workgroup, one-workgroup-per-row kernels
-constexpr int kVecs = 4;          // 16-byte loads per lane per tile
+#ifndef RTOPK_GRID_BLOCK
+#define RTOPK_GRID_BLOCK 512
+#endif
+#ifndef RTOPK_VECS
+#define RTOPK_VECS 4
+#endif
+#ifndef RTOPK_PREFETCH
+#define RTOPK_PREFETCH 1
+#endif
+#ifndef RTOPK_X_NOPHASE2
+#define RTOPK_X_NOPHASE2 0
+#endif
+#ifndef RTOPK_X_NOSTORE
+#define RTOPK_X_NOSTORE 0
+#endif
+#ifndef RTOPK_NO_BARRIER_EXPERIMENT
+#define RTOPK_NO_BARRIER_EXPERIMENT 0
+#endif
+constexpr int kGridBlock = RTOPK_GRID_BLOCK;  // threads per workgroup, many-workgroups-per-row kernels
+constexpr int kRowBlock = 1024;               // threads per workgroup, one-workgroup-per-row kernels
+constexpr int kVecs = RTOPK_VECS;             // 16-byte loads per lane per tile (candidate arrays, fp32 rows)
+template <int DT> constexpr int key_vecs() { return DT == RTOPK_F32 ? RTOPK_VECS : RTOPK_VECS / 2; }  // 16 elements per lane
 
 template <int B>
 struct Shared {
     u32 hist[kMaxBins];
     u32 wsum[B / 64];
     u32 red[2 * (B / 64)];
-    u32 wcnt[2][B / 64][2];
     u32 sel;
+    u32 runW, runC;                   // next free output / candidate position of this workgroup's range
+    uint2 wbuf[B / 64][kStageCap];    // per-wave staged winners    (raw bits, index)
+    uint2 cbuf[B / 64][kStageCap];    // per-wave staged candidates (raw bits, index)
 };
 
 // Loop state on entry to pass p (Algorithm 1's candidates / k, plus the output fill level).
@@ -110,31 +131,75 @@ __device__ __forceinline__ void write_pass_record(rtopk_row_trace* st, int p, co
 // With many workgroups per row it also adds the histogram to the row's global one and stores the
 // suffix sums for the CLASSIFY sweep.
 // ------------------------------------------------------------------------------------------------
+
+// Digits of vector u of a tile: first-pass fast path for X, generic path for candidate arrays.
+template <int DT, int SRC, class Source>
+__device__ __forceinline__ void vector_digits(const Source& src, const typename Source::Tile& t, int u,
+                                              const DigitCtx& c, u32 (&dg)[Source::E]) {
+    if constexpr (SRC == SRC_RUNTIME)
+        src.template digits<DT>(t, u, c, dg);
+    else
+        src.template digits<SRC>(t, u, c, dg);
+}
+
+// MERGE: aggregate lanes that share the first lane's digit before the LDS atomic (pays when one bin
+// is hot); otherwise every lane issues its own atomic (cheapest when digits are spread).
+template <bool FULL, bool MERGE, class Source, int DT, int SRC>
+__device__ __forceinline__ void hist_tile(const Source& src, const typename Source::Tile& t, const DigitCtx& c,
+                                          u32* hist, u32 lane) {
+    constexpr int E = Source::E;
+#pragma unroll
+    for (int u = 0; u < Source::kSlots / E; ++u) {
+        u32 dg[E];
+        vector_digits<DT, SRC>(src, t, u, c, dg);
+#pragma unroll
+        for (int j = 0; j < E; ++j) {
+            if (FULL) {
+                if (MERGE) hist_add(hist, dg[j], lane); else hist_add_plain(hist, dg[j]);
+            } else {
+                u32 raw, idx;
+                bool valid;
+                src.get(t, u * E + j, raw, idx, valid);
+                if (valid) {
+                    if (MERGE) hist_add(hist, dg[j], lane); else hist_add_plain(hist, dg[j]);
+                }
+            }
+        }
+    }
+}
+
+// How many lanes of this wave share the first lane's digit for the tile's first element: a cheap
+// probe of how skewed the digits are (Section 4.2: clustered inputs pile into one bin).
+template <class Source, int DT, int SRC>
+__device__ __forceinline__ u32 hot_lanes(const Source& src, const typename Source::Tile& t, const DigitCtx& c) {
+    u32 dg[Source::E];
+    vector_digits<DT, SRC>(src, t, 0, c, dg);
+    const u32 d0 = __builtin_amdgcn_readfirstlane(dg[0]);
+    return (u32)__popcll(ballot64(dg[0] == d0));
+}
+
 template <class Source, int DT, int SRC, int B, bool SINGLE>
 __device__ __forceinline__ void hist_phase(const Source& src, const Params& P, int p, int row, u32 wg, u32 G,
                                            float a_s, Shared<B>& sm) {
-    const PassInfo pi = P.pass[p];
-    const int nb = 1 << pi.bits;
+    const DigitCtx ctx = make_digit_ctx(P, p, a_s);
+    const int nb = 1 << ctx.pi.bits;
     const u32 tid = threadIdx.x;
+    const u32 lane = lane_id();
     const u32 ntiles = src.ntiles();
     if (!SINGLE && wg >= ntiles) return;  // nothing to count; CLASSIFY ignores this workgroup's record
 
     for (int j = tid; j < nb; j += B) sm.hist[j] = 0;
     __syncthreads();
-    typename Source::Tile cur, nxt;
-    if (wg < ntiles) src.load(wg, tid, cur);
-    for (u32 tile = wg; tile < ntiles; tile += G) {
-        const bool more = tile + G < ntiles;
-        if (more) src.load(tile + G, tid, nxt);  // next tile's loads fly while this one is counted
-#pragma unroll
-        for (int s = 0; s < Source::kSlots; ++s) {
-            u32 raw, idx;
-            bool valid;
-            src.get(cur, s, raw, idx, valid);
-            if (valid) hist_add(sm.hist, digit_of<DT, SRC>(pi, raw, idx, P.dirmask, P.idx_max, a_s));
+    for_each_tile<SINGLE ? 1 : 2>(src, wg, G, ntiles, [&](const typename Source::Tile& cur) {
+        const bool merge = hot_lanes<Source, DT, SRC>(src, cur, ctx) >= 12u;  // wave-uniform
+        if (cur.full) {
+            if (merge) hist_tile<true, true, Source, DT, SRC>(src, cur, ctx, sm.hist, lane);
+            else hist_tile<true, false, Source, DT, SRC>(src, cur, ctx, sm.hist, lane);
+        } else {
+            if (merge) hist_tile<false, true, Source, DT, SRC>(src, cur, ctx, sm.hist, lane);
+            else hist_tile<false, false, Source, DT, SRC>(src, cur, ctx, sm.hist, lane);
         }
-        if (more) cur = nxt;
-    }
+    });
     __syncthreads();
     if (!SINGLE) {
         u32* ghist = P.ghist + ((size_t)(p & 1) * P.batch + row) * kMaxBins;
@@ -162,22 +227,157 @@ __device__ __forceinline__ void store_value(void* out_row, u32 pos, u32 raw) {
         ((uint16_t*)out_row)[pos] = (uint16_t)raw;
 }
 
+// Where one workgroup's share of a pass goes, and how elements are classified.
+template <int DT>
+struct ClassifyOut {
+    void* out_v;         // row's output values
+    long long* out_i;    // row's output indices
+    uint2* cand_out;     // row's next candidate array
+    u32 kk, ncap;        // capacities (writes beyond them are dropped; they never happen in a consistent run)
+    // integer mode: an element wins iff (int)digit > bw (bin, or bin - 1 when the whole bin wins) and stays a
+    // candidate iff digit == b and it does not win
+    int bw;
+    u32 b;
+    // float mode (first pass over X only): the same two tests as comparisons of the element itself with the
+    // numbers whose keys are the bin's boundaries:  win = (x < t1) ^ flip,  at-least-candidate = (x < t2) ^ flip
+    float t1, t2;
+    u64 flip;            // all ones for "largest" (tests become "not less than", true for NaN), 0 for "smallest"
+};
+
+// The number whose ordered key is T, if comparing with it reproduces "key < T" for every element.
+// That fails when T is 0 or 2^32 (no such number), when the bit pattern is a NaN, and at the boundary between
+// the zeros (a float comparison cannot tell -0 from +0).  T is a multiple of 2^16 for 16-bit types.
+template <int DT>
+__device__ __forceinline__ bool threshold_number(u64 T, float* out) {
+    if (T == 0 || T >= (1ull << 32) || T == 0x80000000ull) return false;
+    const u32 t = (u32)T;
+    if (DT == RTOPK_F16) {
+        const u32 t16 = t >> 16;
+        const u32 bits = (t16 & 0x8000u) ? (t16 ^ 0x8000u) : (~t16 & 0xffffu);
+        if ((bits & 0x7fffu) > 0x7c00u) return false;
+        *out = (float)__builtin_bit_cast(_Float16, (uint16_t)bits);
+        return true;
+    }
+    const u32 bits = (t & 0x80000000u) ? (t ^ 0x80000000u) : ~t;
+    if ((bits & 0x7fffffffu) > 0x7f800000u) return false;
+    *out = __uint_as_float(bits);
+    return true;
+}
+
+// Winner / candidate lane masks of slot s of a tile.
+template <bool FULL, bool FLOATCMP, class Source, int DT, int SRC>
+__device__ __forceinline__ void slot_masks(const Source& src, const typename Source::Tile& t, int s, const DigitCtx& c,
+                                           const ClassifyOut<DT>& o, u64& mw, u64& mc) {
+    u64 vm = ~0ull;
+    if (!FULL) {
+        u32 raw, idx;
+        bool valid;
+        src.get(t, s, raw, idx, valid);
+        vm = ballot64(valid);
+    }
+    if constexpr (FLOATCMP) {
+        const float x = src.template value<SRC>(t, s, c.a_s);
+        mw = (ballot64(x < o.t1) ^ o.flip) & vm;
+        mc = (ballot64(x < o.t2) ^ o.flip) & vm & ~mw;
+    } else {
+        u32 dg[Source::E];
+        vector_digits<DT, SRC>(src, t, s / Source::E, c, dg);  // shared by the slots of one vector
+        const u32 d = dg[s % Source::E];
+        mw = ballot64((int)d > o.bw) & vm;
+        mc = ballot64(d == o.b) & vm & ~mw;
+    }
+}
+
+// Write-back of the LDS write buffers (Section 3.1.2).  Every wave stages its survivors in a private
+// LDS buffer and, when the buffer cannot take another 64, reserves a range with one LDS atomic on
+// the workgroup's running position (the workgroup's whole range is known exactly beforehand, so no
+// global atomic is involved) and writes the buffer out as one burst of consecutive addresses.
+// Which wave gets which part of the workgroup's range depends on timing: the ORDER of the outputs
+// may differ between runs, the selected set does not.
+template <int DT>
+__device__ __forceinline__ void flush_wave_winners(const ClassifyOut<DT>& o, const uint2* buf, u32* run, u32 fill,
+                                                   u32 lane) {
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    u32 base = 0;
+    if (lane == 0) base = atomicAdd(run, fill);
+    base = __builtin_amdgcn_readfirstlane(base);
+    for (u32 i = lane; i < fill; i += 64) {
+        const uint2 e = buf[i];
+        const u32 pos = base + i;
+        if (pos < o.kk) {
+            store_value<DT>(o.out_v, pos, e.x);
+            o.out_i[pos] = (long long)e.y;
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+}
+template <int DT>
+__device__ __forceinline__ void flush_wave_candidates(const ClassifyOut<DT>& o, const uint2* buf, u32* run, u32 fill,
+                                                      u32 lane) {
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    u32 base = 0;
+    if (lane == 0) base = atomicAdd(run, fill);
+    base = __builtin_amdgcn_readfirstlane(base);
+    for (u32 i = lane; i < fill; i += 64) {
+        const u32 pos = base + i;
+        if (pos < o.ncap) o.cand_out[pos] = buf[i];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+}
+
+// Entries waiting in this wave's LDS buffers (wave-uniform).
+struct WriteState {
+    u32 fillW, fillC;
+};
+
+// One tile, one sweep over its slots: classify, append survivors to the wave's buffers.
+template <bool FULL, bool FLOATCMP, class Source, int DT, int SRC, int B>
+__device__ __forceinline__ void classify_tile(const Source& src, const typename Source::Tile& t, const DigitCtx& c,
+                                              const ClassifyOut<DT>& o, Shared<B>& sm, u32 lane, u32 wave,
+                                              WriteState& ws) {
+    constexpr int E = Source::E;
+    constexpr int S = Source::kSlots;
+    uint2* wbuf = sm.wbuf[wave];
+    uint2* cbuf = sm.cbuf[wave];
+    const u64 me_bit = 1ull << lane;
+#pragma unroll
+    for (int s = 0; s < S; ++s) {
+        u64 mw, mc;
+        slot_masks<FULL, FLOATCMP, Source, DT, SRC>(src, t, s, c, o, mw, mc);
+        if (mw | mc) {
+            u32 raw, idx;
+            bool valid;
+            src.get(t, s, raw, idx, valid);
+            if (mw) {
+                if (mw & me_bit) wbuf[ws.fillW + mbcnt64(mw)] = make_uint2(raw, idx);
+                ws.fillW += (u32)__popcll(mw);
+                if (ws.fillW > (u32)(kStageCap - 64)) {
+                    flush_wave_winners<DT>(o, wbuf, &sm.runW, ws.fillW, lane);
+                    ws.fillW = 0;
+                }
+            }
+            if (mc) {
+                if (mc & me_bit) cbuf[ws.fillC + mbcnt64(mc)] = make_uint2(raw, idx);
+                ws.fillC += (u32)__popcll(mc);
+                if (ws.fillC > (u32)(kStageCap - 64)) {
+                    flush_wave_candidates<DT>(o, cbuf, &sm.runC, ws.fillC, lane);
+                    ws.fillC = 0;
+                }
+            }
+        }
+    }
+}
+
 template <class Source, int DT, int SRC, int B, bool SINGLE>
 __device__ __forceinline__ void classify_phase(const Source& src, const Params& P, int p, int row, u32 wg, u32 G,
                                                const PassEntry& e, rtopk_row_trace* st, Shared<B>& sm, u32 where) {
-    const PassInfo pi = P.pass[p];
-    const int nb = 1 << pi.bits;
+    const DigitCtx ctx = make_digit_ctx(P, p, st->a_s);
+    const int nb = 1 << ctx.pi.bits;
     const u32 tid = threadIdx.x;
     const u32 lane = lane_id();
     const u32 wave = tid >> 6;
-    constexpr int NW = B / 64;
-    const float a_s = st->a_s;
     const u32 ntiles = src.ntiles();
-    const u32 kk = (u32)P.k;
-    const u32 ncap = (u32)P.n;
 
-    typename Source::Tile cur, nxt;
-    if (wg < ntiles) src.load(wg, tid, cur);  // first tile's loads fly during the selection below
 
     u32 runW = e.out_before, runC = 0;
     if (!SINGLE) {
@@ -209,79 +409,66 @@ __device__ __forceinline__ void classify_phase(const Source& src, const Params& 
             for (int j = tid; j < kMaxBins; j += B) other[j] = 0;
         }
     }
-    if (wg == 0 && tid == 0) write_pass_record(st, p, pi, e, sel, where);
+    if (wg == 0 && tid == 0) write_pass_record(st, p, ctx.pi, e, sel, where);
 
-    void* out_v = (char*)P.out_values + (size_t)row * (size_t)P.k * KeyOf<DT>::kBytes;
-    long long* out_i = P.out_indices + (size_t)row * (size_t)P.k;
-    uint2* cand_out = P.cand[p & 1] + (size_t)row * (size_t)P.n;
-    const u32 b = sel.bin;
-    const bool emit_all = sel.emit_all;
-
-    u32 parity = 0;
-    for (u32 tile = wg; tile < ntiles; tile += G) {
-        const bool more = tile + G < ntiles;
-        if (more) src.load(tile + G, tid, nxt);
-        u32 winbits = 0, candbits = 0, totW = 0, totC = 0;
-#pragma unroll
-        for (int s = 0; s < Source::kSlots; ++s) {
-            u32 raw, idx;
-            bool valid;
-            src.get(cur, s, raw, idx, valid);
-            const u32 dg = digit_of<DT, SRC>(pi, raw, idx, P.dirmask, P.idx_max, a_s);
-            const bool eq = valid && dg == b;
-            const bool w = valid && (dg > b || (emit_all && eq));
-            const bool c = eq && !emit_all;
-            winbits |= (w ? 1u : 0u) << s;
-            candbits |= (c ? 1u : 0u) << s;
-            totW += (u32)__popcll(ballot64(w));
-            totC += (u32)__popcll(ballot64(c));
-        }
-        if (lane == 0) {
-            sm.wcnt[parity][wave][0] = totW;
-            sm.wcnt[parity][wave][1] = totC;
-        }
-        __syncthreads();
-        u32 preW = 0, preC = 0, allW = 0, allC = 0;
-#pragma unroll
-        for (int w2 = 0; w2 < NW; ++w2) {
-            const u32 cw = sm.wcnt[parity][w2][0], cc = sm.wcnt[parity][w2][1];
-            if ((u32)w2 < wave) { preW += cw; preC += cc; }
-            allW += cw;
-            allC += cc;
-        }
-        u32 posW = runW + preW, posC = runC + preC;
-        if (totW | totC) {
-#pragma unroll
-            for (int s = 0; s < Source::kSlots; ++s) {
-                const bool w = (winbits >> s) & 1u;
-                const bool c = (candbits >> s) & 1u;
-                const u64 mw = ballot64(w);
-                const u64 mc = ballot64(c);
-                if (mw | mc) {
-                    u32 raw, idx;
-                    bool valid;
-                    src.get(cur, s, raw, idx, valid);
-                    if (w) {
-                        const u32 pos = posW + mbcnt64(mw);
-                        if (pos < kk) {
-                            store_value<DT>(out_v, pos, raw);
-                            out_i[pos] = (long long)idx;
-                        }
-                    }
-                    if (c) {
-                        const u32 pos = posC + mbcnt64(mc);
-                        if (pos < ncap) cand_out[pos] = make_uint2(raw, idx);
-                    }
-                    posW += (u32)__popcll(mw);
-                    posC += (u32)__popcll(mc);
-                }
+    ClassifyOut<DT> o;
+    o.out_v = (char*)P.out_values + (size_t)row * (size_t)P.k * KeyOf<DT>::kBytes;
+    o.out_i = P.out_indices + (size_t)row * (size_t)P.k;
+    o.cand_out = P.cand[p & 1] + (size_t)row * (size_t)P.n;
+    o.kk = (u32)P.k;
+    o.ncap = (u32)P.n;
+    o.b = sel.bin;
+    o.bw = sel.emit_all ? (int)sel.bin - 1 : (int)sel.bin;
+    // First pass over X: the digit is the key's top bits, so "digit > b" and "digit >= b" are comparisons of
+    // the element with two numbers -- two instructions per element instead of the whole key transform.
+    bool floatcmp = false;
+    o.t1 = o.t2 = 0.0f;
+    o.flip = 0;
+    if constexpr (SRC != SRC_RUNTIME) {
+        const bool largest = P.dirmask == 0;
+        const u32 maxd = (1u << ctx.pi.bits) - 1u;
+        const u64 Bo = largest ? sel.bin : maxd - sel.bin;  // the chosen bin in the uncomplemented key domain
+        const u64 Ta = Bo << ctx.pi.shift, Tb = (Bo + 1) << ctx.pi.shift;
+        float ta, tb;
+        if (threshold_number<DT>(Ta, &ta) && threshold_number<DT>(Tb, &tb)) {
+            floatcmp = true;
+            if (largest) {  // win: key >= Tb (Ta if the whole bin wins); at least candidate: key >= Ta
+                o.t1 = sel.emit_all ? ta : tb;
+                o.t2 = ta;
+                o.flip = ~0ull;
+            } else {        // win: key < Ta (Tb if the whole bin wins); at least candidate: key < Tb
+                o.t1 = sel.emit_all ? tb : ta;
+                o.t2 = tb;
             }
         }
-        runW += allW;
-        runC += allC;
-        parity ^= 1u;
-        if (more) cur = nxt;
     }
+
+    if (tid == 0) {
+        sm.runW = runW;
+        sm.runC = runC;
+    }
+    __syncthreads();
+    WriteState ws;
+    ws.fillW = ws.fillC = 0;
+    for_each_tile<SINGLE ? 1 : 2>(src, wg, G, ntiles, [&](const typename Source::Tile& cur) {
+        if constexpr (SRC != SRC_RUNTIME) {
+            if (floatcmp && cur.full)
+                classify_tile<true, true, Source, DT, SRC, B>(src, cur, ctx, o, sm, lane, wave, ws);
+            else if (floatcmp)
+                classify_tile<false, true, Source, DT, SRC, B>(src, cur, ctx, o, sm, lane, wave, ws);
+            else if (cur.full)
+                classify_tile<true, false, Source, DT, SRC, B>(src, cur, ctx, o, sm, lane, wave, ws);
+            else
+                classify_tile<false, false, Source, DT, SRC, B>(src, cur, ctx, o, sm, lane, wave, ws);
+        } else {
+            if (cur.full)
+                classify_tile<true, false, Source, DT, SRC, B>(src, cur, ctx, o, sm, lane, wave, ws);
+            else
+                classify_tile<false, false, Source, DT, SRC, B>(src, cur, ctx, o, sm, lane, wave, ws);
+        }
+    });
+    if (ws.fillW) flush_wave_winners<DT>(o, sm.wbuf[wave], &sm.runW, ws.fillW, lane);
+    if (ws.fillC) flush_wave_candidates<DT>(o, sm.cbuf[wave], &sm.runC, ws.fillC, lane);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -329,23 +516,23 @@ __device__ __forceinline__ bool multi_runs_pass(const Params& P, const PassEntry
     return e.prev_multi && !e.finished && e.cand > P.small;
 }
 
-template <int DT, int SRC>
+template <int DT, int SRC, bool NT>
 __global__ void __launch_bounds__(kGridBlock) k_hist_keys(Params P) {
     __shared__ Shared<kGridBlock> sm;
     const int row = blockIdx.y;
     const rtopk_row_trace* st = row_state(P, row);
-    KeySource<DT, kGridBlock, kVecs> src;
+    KeySource<DT, kGridBlock, key_vecs<DT>(), NT> src;
     src.init(P.keys, P.n, row);
     hist_phase<decltype(src), DT, SRC, kGridBlock, false>(src, P, 0, row, blockIdx.x, gridDim.x, st->a_s, sm);
 }
 
-template <int DT, int SRC>
+template <int DT, int SRC, bool NT>
 __global__ void __launch_bounds__(kGridBlock) k_classify_keys(Params P) {
     __shared__ Shared<kGridBlock> sm;
     const int row = blockIdx.y;
     rtopk_row_trace* st = row_state(P, row);
     const PassEntry e = pass_entry(P, st, 0);
-    KeySource<DT, kGridBlock, kVecs> src;
+    KeySource<DT, kGridBlock, key_vecs<DT>(), NT> src;
     src.init(P.keys, P.n, row);
     classify_phase<decltype(src), DT, SRC, kGridBlock, false>(src, P, 0, row, blockIdx.x, gridDim.x, e, st, sm, 1u);
 }
@@ -416,7 +603,7 @@ __global__ void __launch_bounds__(kRowBlock) k_row(Params P) {
     __syncthreads();
     {
         const PassEntry e = pass_entry(P, st, 0);
-        KeySource<DT, kRowBlock, kVecs> src;
+        KeySource<DT, kRowBlock, key_vecs<DT>(), false> src;
         src.init(P.keys, P.n, row);
         hist_phase<decltype(src), DT, SRC, kRowBlock, true>(src, P, 0, row, 0u, 1u, st->a_s, sm);
         classify_phase<decltype(src), DT, SRC, kRowBlock, true>(src, P, 0, row, 0u, 1u, e, st, sm, 3u);
@@ -468,7 +655,7 @@ static rtopk_status make_config(int64_t batch, int64_t n, int64_t k, rtopk_dtype
     }
     if (path == 2 && batch > 65535) return RTOPK_ERR_INVALID_ARG;  // rows are the grid's y dimension
     const int eb = elem_bytes(dt);
-    const int64_t tile_elems = (int64_t)kGridBlock * kVecs * (16 / eb);
+    const int64_t tile_elems = (int64_t)kGridBlock * kVecs * 4;  // 16 elements per lane for every type
     const int64_t ntiles = (n + 16 / eb - 1 + tile_elems) / tile_elems;  // one spare for the lead-in
     if (path == 2) {
         if (G == 0) {
@@ -546,12 +733,19 @@ static rtopk_status launch_all(const Params& P, const Config& c, bool scaled, hi
     }
     const dim3 grid(c.G, batch), block(kGridBlock);
     hipLaunchKernelGGL((k_init<DT>), dim3(batch), dim3(256), 0, st, P);
-    if (scaled) {
-        hipLaunchKernelGGL((k_hist_keys<DT, SRC_SCALED>), grid, block, 0, st, P);
-        hipLaunchKernelGGL((k_classify_keys<DT, SRC_SCALED>), grid, block, 0, st, P);
+    const bool nt = (P.flags & kInternalStream) != 0;
+    if (scaled && nt) {
+        hipLaunchKernelGGL((k_hist_keys<DT, SRC_SCALED, true>), grid, block, 0, st, P);
+        hipLaunchKernelGGL((k_classify_keys<DT, SRC_SCALED, true>), grid, block, 0, st, P);
+    } else if (scaled) {
+        hipLaunchKernelGGL((k_hist_keys<DT, SRC_SCALED, false>), grid, block, 0, st, P);
+        hipLaunchKernelGGL((k_classify_keys<DT, SRC_SCALED, false>), grid, block, 0, st, P);
+    } else if (nt) {
+        hipLaunchKernelGGL((k_hist_keys<DT, SRC_KEY, true>), grid, block, 0, st, P);
+        hipLaunchKernelGGL((k_classify_keys<DT, SRC_KEY, true>), grid, block, 0, st, P);
     } else {
-        hipLaunchKernelGGL((k_hist_keys<DT, SRC_KEY>), grid, block, 0, st, P);
-        hipLaunchKernelGGL((k_classify_keys<DT, SRC_KEY>), grid, block, 0, st, P);
+        hipLaunchKernelGGL((k_hist_keys<DT, SRC_KEY, false>), grid, block, 0, st, P);
+        hipLaunchKernelGGL((k_classify_keys<DT, SRC_KEY, false>), grid, block, 0, st, P);
     }
     for (int p = 1; p < c.npass; ++p) {
         hipLaunchKernelGGL((k_hist_cand<DT>), grid, block, 0, st, P, p);
@@ -625,6 +819,8 @@ rtopk_status rtopk_select_ex(const void* keys, int64_t batch, int64_t n, int64_t
     P.small = c.small;
     P.npass = c.npass;
     P.flags = flags;
+    // two sweeps over more data than the 256 MB last-level cache holds: stream it past the caches
+    if ((size_t)batch * (size_t)n * (size_t)eb > ((size_t)384 << 20)) P.flags |= kInternalStream;
     P.seed = seed;
     for (int i = 0; i < c.npass; ++i) P.pass[i] = c.pass[i];
 
