@@ -1,0 +1,184 @@
+#!/usr/bin/env python3
+"""Benchmark of the radix top-k hot path on one MI355X.
+
+A "step" is one complete selection (every kernel of the path: first-pass histogram sweep, first-pass
+classify sweep, later digit passes, single-workgroup finish) over one batch of synthetic input that is
+already resident in HBM.  The workload is the benchmark's headline case that fits one GPU:
+
+    config 4: single query, n = 2^28 fp32 keys i.i.d. uniform in [-1e6, 1e6), k = 2^20, largest
+
+Prints ONE JSON line:  keys/sec over the timed region, the roofline of the dominant kernel (measured live
+with HIP events recorded by the library on the launch stream) and the CPU oracle timed on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--log2n", type=int, default=28, help="row length 2^log2n (default: the headline 2^28)")
+    ap.add_argument("--log2k", type=int, default=20)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-batch-case", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not supported"
+              % args.gpus, file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2501_14336_amd import binding as B
+    from paper_2501_14336_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        return 2
+    B.load()
+    dev = torch.device("cuda:0")
+    n, k = 1 << args.log2n, 1 << args.log2k
+    steps, warmup = args.steps, args.warmup
+
+    # ---- workload: config 4, generated on the host by the seeded generator, then made resident
+    x_host = W.config4(n)
+    x = torch.from_numpy(x_host).to(dev)[None, :]
+    vals = torch.empty((1, k), dtype=torch.float32, device=dev)
+    idx = torch.empty((1, k), dtype=torch.int64, device=dev)
+    ws = torch.empty(B.rtopk_workspace_bytes(1, n, k, B.RTOPK_F32), dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream(dev)
+
+    def make_events(count):
+        evs = []
+        for _ in range(count):
+            e = torch.cuda.Event(enable_timing=True)
+            e.record(stream)  # instantiates the underlying hipEvent_t
+            evs.append(e)
+        return evs
+
+    for _ in range(warmup):
+        B.topk(x, k, True, workspace=ws, out=(vals, idx))
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly `steps` steps.  On every 4th step the library records 5 HIP events on the
+    # launch stream around the two sweeps (an event costs a few microseconds of stream time, so not on all).
+    sampled = [i for i in range(steps) if i % 4 == 0]
+    per_step = {i: make_events(B.RTOPK_NUM_EVENTS) for i in sampled}
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        evs = per_step.get(i)
+        B.topk(x, k, True, workspace=ws, out=(vals, idx), events=[e.cuda_event for e in evs] if evs else None)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    per_step = list(per_step.values())
+    wall_ms = (t1 - t0) * 1e3
+    ms_per_step = wall_ms / steps
+    keys_per_s = n * steps / (t1 - t0)
+
+    hist_ms = float(np.mean([evs[1].elapsed_time(evs[2]) for evs in per_step]))
+    classify_ms = float(np.mean([evs[2].elapsed_time(evs[3]) for evs in per_step]))
+    call_ms = float(np.mean([evs[0].elapsed_time(evs[4]) for evs in per_step]))
+
+    # ---- algorithmic bytes from the run's own pass records
+    tr = B.read_trace(ws, 1)[0]
+    assert tr.error == 0 and tr.done, "device reported an inconsistent state"
+    p0 = tr.passes[0]
+    es = 4
+    hist_bytes = es * n                                               # first-pass HIST reads X once
+    classify_bytes = es * n + 8 * p0.cand_after + (es + 8) * p0.winners  # reads X, writes candidates + winners
+    later = sum(2 * 8 * p.cand_before + 8 * p.cand_after + (es + 8) * p.winners for p in tr.passes[1:])
+    path_bytes = hist_bytes + classify_bytes + later                  # every pass, as executed
+    floor_bytes = 2 * es * n + (es + 8) * k                           # two sweeps + the output
+    dominant = ("classify_keys", classify_ms, classify_bytes) if classify_ms >= hist_ms else \
+               ("hist_keys", hist_ms, hist_bytes)
+    achieved = dominant[2] / (dominant[1] * 1e-3) / 1e9
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic_config4.json")
+    if os.path.exists(tpath) and args.log2n == 28 and args.log2k == 20:
+        try:
+            traffic = json.load(open(tpath)).get(dominant[0] + "_bytes_per_launch")
+        except Exception:
+            traffic = None
+
+    out = {
+        "metric": "top-k keys/sec (single query n=2^28 fp32, k=2^20) and % of HBM peak BW",
+        "value": keys_per_s,
+        "unit": "keys/s",
+        "n_gpus": 1,
+        "steps": steps,
+        "warmup": warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "config4: 1 x 2^%d fp32 U[-1e6,1e6) seed 4000, k=2^%d, largest, int64 indices"
+                               % (args.log2n, args.log2k),
+                   "batch": 1, "n": n, "k": k},
+        "roofline": {"bound": "hbm", "kernel": dominant[0], "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "kernel_ms": dominant[1], "algorithmic_bytes": dominant[2]},
+        "whole_path": {"gpu_ms_per_call": call_ms, "hist_keys_ms": hist_ms, "classify_keys_ms": classify_ms,
+                       "bytes_moved_by_all_passes": path_bytes, "floor_bytes_two_sweeps_plus_output": floor_bytes,
+                       "achieved_frac_of_hbm_peak": path_bytes / (call_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                       "algorithmic_frac_of_hbm_peak": floor_bytes / (call_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                       "passes": [[p.where, p.cand_before, p.cand_after, p.winners] for p in tr.passes]},
+    }
+
+    # ---- the batch shape of the metric: 1024 x 2^17 bf16 logits, k = 50 (reported, not the headline value)
+    if not args.no_batch_case:
+        del x
+        xb = torch.from_numpy(W.config3().view(np.int16)).to(dev).view(torch.bfloat16)
+        kb = 50
+        wsb = torch.empty(B.rtopk_workspace_bytes(1024, 131072, kb, B.RTOPK_BF16), dtype=torch.uint8, device=dev)
+        vb = torch.empty((1024, kb), dtype=torch.bfloat16, device=dev)
+        ib = torch.empty((1024, kb), dtype=torch.int64, device=dev)
+        for _ in range(warmup):
+            B.topk(xb, kb, True, workspace=wsb, out=(vb, ib))
+        torch.cuda.synchronize()
+        tb0 = time.perf_counter()
+        for _ in range(steps):
+            B.topk(xb, kb, True, workspace=wsb, out=(vb, ib))
+        torch.cuda.synchronize()
+        tb = (time.perf_counter() - tb0) / steps
+        bb = 2 * 2 * 1024 * 131072 + (2 + 8) * 1024 * kb
+        out["batch_case"] = {"workload": "config3: 1024 x 131072 bf16 logits N(0,9)+8 spikes, k=50, largest",
+                             "keys_per_s": 1024 * 131072 / tb, "ms_per_step": tb * 1e3,
+                             "algorithmic_frac_of_hbm_peak": bb / tb / 1e9 / HBM_PEAK_GBS}
+        del xb, wsb
+
+    # ---- CPU baseline: the oracle as it stands, on a bounded sample of the same workload
+    if not args.no_cpu_baseline:
+        import oracle
+        ns = min(n, 1 << 24)
+        ks = max(1, ns * k // n)
+        sample = x_host[:ns]
+        c0 = time.perf_counter()
+        oracle.topk(sample, oracle.F32, ks, True)
+        cs = time.perf_counter() - c0
+        out["cpu_baseline"] = {"value": ns / cs, "unit": "keys/s", "cores": 1, "kind": "oracle",
+                               "sample": "first 2^%d keys of the same dataset, k=%d (same k/n), full sort of "
+                                         "(value, index) pairs, single thread, %.1f s" % (ns.bit_length() - 1, ks, cs)}
+
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -60,7 +60,7 @@ enum {
  * code path on the same input.  A field left 0 means "library default".
  */
 typedef struct {
-    int32_t digit_bits;      /* radix digit width d, 4..12 (default 12 for fp32, 11 for 16-bit keys)           */
+    int32_t digit_bits;      /* radix digit width d, 8..12 (default 12 for fp32, 11 for 16-bit keys)           */
     int32_t path;            /* 0 auto, 1 one workgroup per row (fused kernel), 2 many workgroups per row      */
     int32_t wgs_per_row;     /* workgroups cooperating on one row in path 2 (default: fill 256 CUs)            */
     int32_t small_threshold; /* candidate count at or below which one workgroup finishes a row by itself       */
@@ -106,6 +106,23 @@ rtopk_status rtopk_select_ex(const void* keys, int64_t batch, int64_t n, int64_t
                              uint32_t flags, uint64_t seed, void* out_values, int64_t* out_indices,
                              void* workspace, size_t workspace_bytes, void* hip_stream,
                              const rtopk_tuning* tuning);
+
+/*
+ * Profiling variant of rtopk_select_ex: additionally records caller-created HIP events (hipEvent_t handles,
+ * host array `events` of RTOPK_NUM_EVENTS entries, NULL entries are skipped) on `hip_stream` at fixed points,
+ * so that a harness can time the two sweeps over the input (the countBin and selectCandidate/filter sweeps of
+ * paper Section 2.3.1, which dominate the run time, Section 3.2.1) without an external profiler:
+ *   events[0] before anything is enqueued          events[1] before the first-pass HIST kernel
+ *   events[2] between first-pass HIST and CLASSIFY  events[3] after the first-pass CLASSIFY kernel
+ *   events[4] after the last kernel
+ * With one workgroup per row (a single fused kernel) events[1..3] are recorded together with events[0].
+ * Nothing is synchronised; the caller reads the events after the stream has drained.
+ */
+#define RTOPK_NUM_EVENTS 5
+rtopk_status rtopk_select_events(const void* keys, int64_t batch, int64_t n, int64_t k, rtopk_dtype dt, int largest,
+                                 uint32_t flags, uint64_t seed, void* out_values, int64_t* out_indices,
+                                 void* workspace, size_t workspace_bytes, void* hip_stream,
+                                 const rtopk_tuning* tuning, void* const* events);
 
 /*
  * Per-pass record of the last rtopk_select that used `workspace`, for tests and profiling:

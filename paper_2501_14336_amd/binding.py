@@ -25,6 +25,7 @@ EXPORTS = (
     "rtopk_workspace_bytes",
     "rtopk_select",
     "rtopk_select_ex",
+    "rtopk_select_events",
     "rtopk_status_string",
     "rtopk_version",
 )
@@ -82,17 +83,32 @@ class RtopkError(RuntimeError):
         self.status = status
 
 
+_SOURCES = ("rtopk_api.hip", "rtopk_f32.hip", "rtopk_f16.hip", "rtopk_bf16.hip")
+_HEADERS = ("rtopk_device.h", "rtopk_host.h", "rtopk_kernels.inl")
+
+
 def build(force: bool = True) -> str:
-    """Compile csrc/ for gfx950 into librtopk.so next to this file (hipcc cross-compiles without a GPU)."""
-    srcs = [os.path.join(_SRC_DIR, "rtopk_kernels.hip")]
-    deps = srcs + [os.path.join(_SRC_DIR, "rtopk_device.h"), os.path.join(_ROOT, "include", "rtopk.h")]
+    """Compile csrc/ for gfx950 into librtopk.so next to this file (hipcc cross-compiles without a GPU).
+    The kernels are instantiated once per key type in separate translation units, compiled in parallel."""
+    srcs = [os.path.join(_SRC_DIR, f) for f in _SOURCES]
+    deps = srcs + [os.path.join(_SRC_DIR, f) for f in _HEADERS] + [os.path.join(_ROOT, "include", "rtopk.h")]
     if not force and os.path.exists(_LIB_PATH) and all(os.path.getmtime(_LIB_PATH) >= os.path.getmtime(d) for d in deps):
         return _LIB_PATH
+    objdir = os.path.join(_HERE, "_build")
+    os.makedirs(objdir, exist_ok=True)
+    common = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
+              "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+              "-I", os.path.join(_ROOT, "include"), "-I", _SRC_DIR]
+    procs, objs = [], []
+    for src in srcs:
+        obj = os.path.join(objdir, os.path.basename(src) + ".o")
+        objs.append(obj)
+        procs.append((src, subprocess.Popen(common + ["-c", src, "-o", obj])))
+    for src, pr in procs:
+        if pr.wait() != 0:
+            raise RuntimeError("hipcc failed on %s" % src)
     tmp = _LIB_PATH + ".tmp%d" % os.getpid()
-    cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
-           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-I", os.path.join(_ROOT, "include"), "-I", _SRC_DIR, "-o", tmp] + srcs
-    subprocess.check_call(cmd)
+    subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + objs)
     os.replace(tmp, _LIB_PATH)
     return _LIB_PATH
 
@@ -104,6 +120,10 @@ def load():
     """Load librtopk.so (built beforehand; built now only if it is missing)."""
     global _lib
     if _lib is None:
+        try:  # PyTorch ships its own HIP runtime: let it be the one this process uses
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         if not os.path.exists(_LIB_PATH):
             build(force=True)
         lib = ctypes.CDLL(_LIB_PATH)
@@ -115,6 +135,8 @@ def load():
         lib.rtopk_select.argtypes = [vp, i64, i64, i64, ctypes.c_int, ctypes.c_int, u32, u64, vp, vp, vp, sz, vp]
         lib.rtopk_select_ex.restype = ctypes.c_int
         lib.rtopk_select_ex.argtypes = lib.rtopk_select.argtypes + [ctypes.POINTER(RtopkTuning)]
+        lib.rtopk_select_events.restype = ctypes.c_int
+        lib.rtopk_select_events.argtypes = lib.rtopk_select_ex.argtypes + [ctypes.POINTER(ctypes.c_void_p)]
         lib.rtopk_status_string.restype = ctypes.c_char_p
         lib.rtopk_status_string.argtypes = [ctypes.c_int]
         lib.rtopk_version.restype = ctypes.c_char_p
@@ -147,12 +169,22 @@ def rtopk_workspace_bytes(batch: int, n: int, k: int, dtype: int, flags: int = 0
     return int(out.value)
 
 
+RTOPK_NUM_EVENTS = 5
+
+
 def rtopk_select(keys_ptr: int, batch: int, n: int, k: int, dtype: int, largest: bool, flags: int, seed: int,
                  out_values_ptr: int, out_indices_ptr: int, workspace_ptr: int, workspace_bytes: int,
-                 stream: int = 0, tuning=None) -> None:
-    """Raw call: device addresses in, nothing allocated, nothing synchronised."""
-    st = load().rtopk_select_ex(keys_ptr, batch, n, k, dtype, 1 if largest else 0, flags, seed, out_values_ptr,
-                                out_indices_ptr, workspace_ptr, workspace_bytes, stream, _tuning_ptr(tuning))
+                 stream: int = 0, tuning=None, events=None) -> None:
+    """Raw call: device addresses in, nothing allocated, nothing synchronised.
+    ``events``: optional sequence of RTOPK_NUM_EVENTS raw hipEvent_t handles (0 = skip), see rtopk_select_events."""
+    if events is None:
+        st = load().rtopk_select_ex(keys_ptr, batch, n, k, dtype, 1 if largest else 0, flags, seed, out_values_ptr,
+                                    out_indices_ptr, workspace_ptr, workspace_bytes, stream, _tuning_ptr(tuning))
+    else:
+        arr = (ctypes.c_void_p * RTOPK_NUM_EVENTS)(*[int(e) if e else None for e in events])
+        st = load().rtopk_select_events(keys_ptr, batch, n, k, dtype, 1 if largest else 0, flags, seed,
+                                        out_values_ptr, out_indices_ptr, workspace_ptr, workspace_bytes, stream,
+                                        _tuning_ptr(tuning), arr)
     if st != RTOPK_OK:
         raise RtopkError(st, rtopk_status_string(st))
 
@@ -167,7 +199,7 @@ def _torch_dtype_code(t):
 
 
 def topk(x, k: int, largest: bool = True, scaling: bool = False, seed: int = 0, tuning=None, workspace=None,
-         out=None):
+         out=None, events=None):
     """Top-k of every row of a CUDA/HIP tensor ``x`` ([n] or [batch, n]; fp32, fp16 or bf16).
 
     Returns (values [batch, k] of x.dtype, indices [batch, k] int64, workspace).  The order inside a row is
@@ -193,7 +225,7 @@ def topk(x, k: int, largest: bool = True, scaling: bool = False, seed: int = 0, 
         vals, idx = out
     stream = torch.cuda.current_stream(x.device).cuda_stream
     rtopk_select(x.data_ptr(), batch, n, k, code, largest, flags, seed, vals.data_ptr(), idx.data_ptr(),
-                 workspace.data_ptr(), workspace.numel(), stream, tuning)
+                 workspace.data_ptr(), workspace.numel(), stream, tuning, events)
     return vals, idx, workspace
 
 

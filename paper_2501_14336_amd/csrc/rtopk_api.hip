@@ -1,0 +1,209 @@
+// C-ABI entry points declared in include/rtopk.h: argument validation, the digit plan, workspace layout,
+// and the hand-off to the per-type kernel launchers.  Host code only.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <string.h>
+
+#include "rtopk.h"
+#include "rtopk_device.h"
+#include "rtopk_host.h"
+
+namespace rtopk {
+
+// ------------------------------------------------------------------------------------------------
+// host side
+// ------------------------------------------------------------------------------------------------
+struct Layout {
+    size_t state_off, ghist_off, bases_off, swg_off, cand0_off, cand1_off, total;
+};
+
+static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+static int elem_bytes(rtopk_dtype dt) { return dt == RTOPK_F32 ? 4 : 2; }
+
+static rtopk_status make_config(int64_t batch, int64_t n, int64_t k, rtopk_dtype dt, int largest, uint32_t flags,
+                                const rtopk_tuning* tn, Config* c) {
+    if (batch < 1 || batch > 0x7fffffff || n < 1 || n > RTOPK_MAX_N || k < 1 || k > n) return RTOPK_ERR_INVALID_ARG;
+    if (dt != RTOPK_F32 && dt != RTOPK_F16 && dt != RTOPK_BF16) return RTOPK_ERR_INVALID_ARG;
+    if (flags & ~(uint32_t)RTOPK_FLAG_SCALING) return RTOPK_ERR_INVALID_ARG;
+    int d = dt == RTOPK_F32 ? 12 : 11;
+    int path = 0, G = 0;
+    u32 small = 32768;
+    if (tn) {
+        if (tn->digit_bits) {
+            if (tn->digit_bits < 8 || tn->digit_bits > 12) return RTOPK_ERR_INVALID_ARG;
+            d = tn->digit_bits;
+        }
+        if (tn->path < 0 || tn->path > 2 || tn->wgs_per_row < 0 || tn->small_threshold < 0) return RTOPK_ERR_INVALID_ARG;
+        path = tn->path;
+        G = tn->wgs_per_row;
+        if (tn->small_threshold) small = (u32)tn->small_threshold;
+    }
+    if (path == 0) {
+        // short rows, or enough rows to occupy every compute unit: one workgroup per row
+        path = (n <= (1 << 18) || (batch >= 256 && n <= (1 << 20))) ? 1 : 2;
+        if (batch > 65535) path = 1;
+    }
+    if (path == 2 && batch > 65535) return RTOPK_ERR_INVALID_ARG;  // rows are the grid's y dimension
+    const int eb = elem_bytes(dt);
+    const int64_t tile_elems = (int64_t)kHostGridBlock * kHostElemsPerLane;  // 16 elements per lane for every type
+    const int64_t ntiles = (n + 16 / eb - 1 + tile_elems) / tile_elems;  // one spare for the lead-in
+    if (path == 2) {
+        if (G == 0) {
+            int64_t want = 512 / batch;  // about two workgroups per compute unit in total
+            if (want < 1) want = 1;
+            G = (int)want;
+        }
+        if (G > ntiles) G = (int)ntiles;
+        if (G > 4096) G = 4096;
+        if (G < 1) G = 1;
+    } else {
+        G = 1;
+    }
+    c->d = d;
+    c->path = path;
+    c->G = G;
+    c->small = small;
+    c->dirmask = largest ? 0u : (dt == RTOPK_F32 ? 0xffffffffu : 0xffff0000u);
+
+    int np = 0;
+    const int kw = dt == RTOPK_F32 ? 32 : 16;
+    if ((flags & RTOPK_FLAG_SCALING) && dt == RTOPK_F32) {
+        for (int hi = 32; hi > 0;) {
+            int bits = d < hi ? d : hi;
+            c->pass[np++] = PassInfo{SRC_SCALED, (u32)(hi - bits), (u32)bits};
+            hi -= bits;
+        }
+    }
+    for (int hi = 32; hi > 32 - kw;) {
+        int bits = d < hi - (32 - kw) ? d : hi - (32 - kw);
+        c->pass[np++] = PassInfo{SRC_KEY, (u32)(hi - bits), (u32)bits};
+        hi -= bits;
+    }
+    int ib = 0;
+    while (((int64_t)1 << ib) < n) ++ib;
+    c->idx_max = ib == 0 ? 0u : (u32)(((u64)1 << ib) - 1);
+    for (int hi = ib; hi > 0;) {
+        int bits = d < hi ? d : hi;
+        c->pass[np++] = PassInfo{SRC_IDX, (u32)(hi - bits), (u32)bits};
+        hi -= bits;
+    }
+    if (np > kMaxPasses) return RTOPK_ERR_INVALID_ARG;
+    c->npass = np;
+    return RTOPK_OK;
+}
+
+static Layout make_layout(int64_t batch, int64_t n, const Config& c) {
+    Layout L;
+    size_t off = 0;
+    L.state_off = off;
+    off = align_up(off + (size_t)batch * RTOPK_TRACE_STRIDE, 256);
+    L.ghist_off = off;
+    off = align_up(off + (size_t)2 * batch * kMaxBins * 4, 256);
+    L.bases_off = off;
+    off = align_up(off + (size_t)batch * c.G * 2 * 4, 256);
+    L.swg_off = off;
+    off = align_up(off + (size_t)batch * c.G * kSwgStride * 4, 256);
+    L.cand0_off = off;
+    off = align_up(off + (size_t)batch * (size_t)n * 8, 256);
+    L.cand1_off = off;
+    off = align_up(off + (size_t)batch * (size_t)n * 8, 256);
+    L.total = off + 256;  // the last 16-byte load of an odd-length candidate array may touch 8 bytes past it
+    return L;
+}
+
+}  // namespace rtopk
+
+using namespace rtopk;
+
+extern "C" {
+
+const char* rtopk_status_string(rtopk_status s) {
+    switch (s) {
+        case RTOPK_OK: return "ok";
+        case RTOPK_ERR_INVALID_ARG: return "invalid argument";
+        case RTOPK_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+        case RTOPK_ERR_UNSUPPORTED: return "unsupported (misaligned buffer)";
+        case RTOPK_ERR_HIP: return "HIP runtime rejected a launch";
+    }
+    return "unknown status";
+}
+
+const char* rtopk_version(void) { return "0.1"; }
+
+rtopk_status rtopk_workspace_bytes(int64_t batch, int64_t n, int64_t k, rtopk_dtype dt, uint32_t flags,
+                                   const rtopk_tuning* tuning, size_t* bytes_out) {
+    if (!bytes_out) return RTOPK_ERR_INVALID_ARG;
+    Config c;
+    rtopk_status s = make_config(batch, n, k, dt, 1, flags, tuning, &c);
+    if (s != RTOPK_OK) return s;
+    *bytes_out = make_layout(batch, n, c).total;
+    return RTOPK_OK;
+}
+
+rtopk_status rtopk_select_events(const void* keys, int64_t batch, int64_t n, int64_t k, rtopk_dtype dt, int largest,
+                                 uint32_t flags, uint64_t seed, void* out_values, int64_t* out_indices,
+                                 void* workspace, size_t workspace_bytes, void* hip_stream,
+                                 const rtopk_tuning* tuning, void* const* events) {
+    if (!keys || !out_values || !out_indices || !workspace) return RTOPK_ERR_INVALID_ARG;
+    Config c;
+    rtopk_status s = make_config(batch, n, k, dt, largest, flags, tuning, &c);
+    if (s != RTOPK_OK) return s;
+    const int eb = elem_bytes(dt);
+    if (((uintptr_t)keys % eb) || ((uintptr_t)out_values % eb) || ((uintptr_t)out_indices % 8) ||
+        ((uintptr_t)workspace % 256))
+        return RTOPK_ERR_UNSUPPORTED;
+    const Layout L = make_layout(batch, n, c);
+    if (workspace_bytes < L.total) return RTOPK_ERR_WORKSPACE_TOO_SMALL;
+
+    Params P;
+    memset(&P, 0, sizeof(P));
+    char* ws = (char*)workspace;
+    P.keys = keys;
+    P.out_values = out_values;
+    P.out_indices = (long long*)out_indices;
+    P.state = (rtopk_row_trace*)(ws + L.state_off);
+    P.ghist = (u32*)(ws + L.ghist_off);
+    P.bases = (u32*)(ws + L.bases_off);
+    P.swg = (u32*)(ws + L.swg_off);
+    P.cand[0] = (uint2*)(ws + L.cand0_off);
+    P.cand[1] = (uint2*)(ws + L.cand1_off);
+    P.n = n;
+    P.k = k;
+    P.batch = (int)batch;
+    P.G = c.G;
+    P.dirmask = c.dirmask;
+    P.idx_max = c.idx_max;
+    P.small = c.small;
+    P.npass = c.npass;
+    P.flags = flags;
+    // two sweeps over more data than the 256 MB last-level cache holds: stream it past the caches
+    if ((size_t)batch * (size_t)n * (size_t)eb > ((size_t)384 << 20)) P.flags |= kInternalStream;
+    P.seed = seed;
+    for (int i = 0; i < c.npass; ++i) P.pass[i] = c.pass[i];
+
+    hipStream_t st = (hipStream_t)hip_stream;
+    const bool scaled = (flags & RTOPK_FLAG_SCALING) && dt == RTOPK_F32;
+    switch (dt) {
+        case RTOPK_F32: return launch_f32(P, c, scaled, st, events);
+        case RTOPK_F16: return launch_f16(P, c, false, st, events);
+        case RTOPK_BF16: return launch_bf16(P, c, false, st, events);
+    }
+    return RTOPK_ERR_INVALID_ARG;
+}
+
+rtopk_status rtopk_select_ex(const void* keys, int64_t batch, int64_t n, int64_t k, rtopk_dtype dt, int largest,
+                             uint32_t flags, uint64_t seed, void* out_values, int64_t* out_indices, void* workspace,
+                             size_t workspace_bytes, void* hip_stream, const rtopk_tuning* tuning) {
+    return rtopk_select_events(keys, batch, n, k, dt, largest, flags, seed, out_values, out_indices, workspace,
+                               workspace_bytes, hip_stream, tuning, nullptr);
+}
+
+rtopk_status rtopk_select(const void* keys, int64_t batch, int64_t n, int64_t k, rtopk_dtype dt, int largest,
+                          uint32_t flags, uint64_t seed, void* out_values, int64_t* out_indices, void* workspace,
+                          size_t workspace_bytes, void* hip_stream) {
+    return rtopk_select_ex(keys, batch, n, k, dt, largest, flags, seed, out_values, out_indices, workspace,
+                           workspace_bytes, hip_stream, nullptr);
+}
+
+}  // extern "C"

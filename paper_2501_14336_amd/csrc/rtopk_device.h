@@ -351,9 +351,9 @@ struct CandSource {
 // software pipeline of DEPTH tiles: DEPTH + 1 register sets take turns, the loads of the next DEPTH tiles
 // are in flight while one is processed, every load in the steady state is unconditional and no register
 // set is ever copied, so the compiler can wait for exactly the oldest set instead of draining the queue.
-// The at most two partial tiles are handled afterwards, unpipelined.  f(tile) is called once per tile.
-template <int DEPTH, class Source, class F>
-__device__ __forceinline__ void for_each_tile(const Source& src, u32 wg, u32 G, u32 ntiles, F&& f) {
+// The at most two partial tiles are handled afterwards, unpipelined, by fedge(tile).
+template <int DEPTH, class Source, class FFull, class FEdge>
+__device__ __forceinline__ void for_each_tile(const Source& src, u32 wg, u32 G, u32 ntiles, FFull&& f, FEdge&& fedge) {
     const u32 tid = threadIdx.x;
     u32 f0, f1;  // tiles [f0, f1) are full
     src.full_range(f0, f1);
@@ -367,33 +367,36 @@ __device__ __forceinline__ void for_each_tile(const Source& src, u32 wg, u32 G, 
             src.load_full(first, tid, a);
             if (m > 1) src.load_full(first + G, tid, b);
             u32 i = 0;
-            for (;;) {
-                if (i + 2 >= m) { f(a); if (i + 1 < m) f(b); break; }
+            // steady state: all three loads of a round exist, so every load is unconditional
+            for (; i + 4 < m; i += 3) {
                 src.load_full(first + (i + 2) * G, tid, c);
                 f(a);
-                ++i;
-                if (i + 2 >= m) { f(b); if (i + 1 < m) f(c); break; }
-                src.load_full(first + (i + 2) * G, tid, a);
+                src.load_full(first + (i + 3) * G, tid, a);
                 f(b);
-                ++i;
-                if (i + 2 >= m) { f(c); if (i + 1 < m) f(a); break; }
-                src.load_full(first + (i + 2) * G, tid, b);
+                src.load_full(first + (i + 4) * G, tid, b);
                 f(c);
-                ++i;
+            }
+            // at most four tiles left; a (and b, if it exists) are loaded
+            f(a);
+            if (i + 1 < m) f(b);
+            for (u32 j = i + 2; j < m; ++j) {
+                src.load_full(first + j * G, tid, a);
+                f(a);
             }
         } else if constexpr (DEPTH == 1) {
             typename Source::Tile a, b;
             src.load_full(first, tid, a);
             u32 i = 0;
-            for (;;) {
-                if (i + 1 >= m) { f(a); break; }
+            for (; i + 2 < m; i += 2) {
                 src.load_full(first + (i + 1) * G, tid, b);
                 f(a);
-                ++i;
-                if (i + 1 >= m) { f(b); break; }
-                src.load_full(first + (i + 1) * G, tid, a);
+                src.load_full(first + (i + 2) * G, tid, a);
                 f(b);
-                ++i;
+            }
+            f(a);
+            if (i + 1 < m) {
+                src.load_full(first + (i + 1) * G, tid, b);
+                f(b);
             }
         } else {
             for (u32 i = 0; i < m; ++i) {
@@ -413,7 +416,7 @@ __device__ __forceinline__ void for_each_tile(const Source& src, u32 wg, u32 G, 
         }
         typename Source::Tile e;
         src.load(t, tid, e);
-        f(e);
+        fedge(e);
     }
 }
 

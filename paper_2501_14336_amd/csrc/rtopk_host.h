@@ -1,0 +1,27 @@
+// Host-side plan of one call: which kernels run, with what geometry.  Shared by the API translation
+// unit and the per-type kernel translation units.
+#pragma once
+#include <hip/hip_runtime.h>
+#include "rtopk.h"
+#include "rtopk_device.h"
+
+namespace rtopk {
+
+struct Config {
+    int d, path, G;
+    u32 small;
+    int npass;
+    u32 idx_max, dirmask;
+    PassInfo pass[kMaxPasses];
+};
+
+// Enqueue every kernel of one call for one key type (defined in rtopk_f32.hip / rtopk_f16.hip / rtopk_bf16.hip).
+rtopk_status launch_f32(const Params& P, const Config& c, bool scaled, hipStream_t st, void* const* events);
+rtopk_status launch_f16(const Params& P, const Config& c, bool scaled, hipStream_t st, void* const* events);
+rtopk_status launch_bf16(const Params& P, const Config& c, bool scaled, hipStream_t st, void* const* events);
+
+// Launch geometry the host needs for sizing.
+constexpr int kHostGridBlock = 512;
+constexpr int kHostElemsPerLane = 16;
+
+}  // namespace rtopk

@@ -1,4 +1,4 @@
-// Radix top-k kernels for gfx950 and the C-ABI entry points declared in include/rtopk.h.
+// Radix top-k kernels for gfx950 (templates; instantiated once per key type by rtopk_f32/f16/bf16.hip).
 //
 // One digit pass (paper Section 2.3.1) is two sweeps over the current candidates:
 //
@@ -26,6 +26,7 @@
 
 #include "rtopk.h"
 #include "rtopk_device.h"
+#include "rtopk_host.h"
 
 namespace rtopk {
 
@@ -35,19 +36,8 @@ namespace rtopk {
 #ifndef RTOPK_VECS
 #define RTOPK_VECS 4
 #endif
-#ifndef RTOPK_PREFETCH
-#define RTOPK_PREFETCH 1
-#endif
-#ifndef RTOPK_X_NOPHASE2
-#define RTOPK_X_NOPHASE2 0
-#endif
-#ifndef RTOPK_X_NOSTORE
-#define RTOPK_X_NOSTORE 0
-#endif
-#ifndef RTOPK_NO_BARRIER_EXPERIMENT
-#define RTOPK_NO_BARRIER_EXPERIMENT 0
-#endif
 constexpr int kGridBlock = RTOPK_GRID_BLOCK;  // threads per workgroup, many-workgroups-per-row kernels
+static_assert(kGridBlock == kHostGridBlock && RTOPK_VECS * 4 == kHostElemsPerLane, "host and device tile geometry differ");
 constexpr int kRowBlock = 1024;               // threads per workgroup, one-workgroup-per-row kernels
 constexpr int kVecs = RTOPK_VECS;             // 16-byte loads per lane per tile (candidate arrays, fp32 rows)
 template <int DT> constexpr int key_vecs() { return DT == RTOPK_F32 ? RTOPK_VECS : RTOPK_VECS / 2; }  // 16 elements per lane
@@ -190,16 +180,17 @@ __device__ __forceinline__ void hist_phase(const Source& src, const Params& P, i
 
     for (int j = tid; j < nb; j += B) sm.hist[j] = 0;
     __syncthreads();
-    for_each_tile<SINGLE ? 1 : 2>(src, wg, G, ntiles, [&](const typename Source::Tile& cur) {
-        const bool merge = hot_lanes<Source, DT, SRC>(src, cur, ctx) >= 12u;  // wave-uniform
-        if (cur.full) {
-            if (merge) hist_tile<true, true, Source, DT, SRC>(src, cur, ctx, sm.hist, lane);
-            else hist_tile<true, false, Source, DT, SRC>(src, cur, ctx, sm.hist, lane);
-        } else {
-            if (merge) hist_tile<false, true, Source, DT, SRC>(src, cur, ctx, sm.hist, lane);
-            else hist_tile<false, false, Source, DT, SRC>(src, cur, ctx, sm.hist, lane);
-        }
-    });
+    for_each_tile<SINGLE ? 1 : 2>(
+        src, wg, G, ntiles,
+        [&](const typename Source::Tile& cur) {
+            if (hot_lanes<Source, DT, SRC>(src, cur, ctx) >= 12u)  // wave-uniform
+                hist_tile<true, true, Source, DT, SRC>(src, cur, ctx, sm.hist, lane);
+            else
+                hist_tile<true, false, Source, DT, SRC>(src, cur, ctx, sm.hist, lane);
+        },
+        [&](const typename Source::Tile& cur) {
+            hist_tile<false, true, Source, DT, SRC>(src, cur, ctx, sm.hist, lane);
+        });
     __syncthreads();
     if (!SINGLE) {
         u32* ghist = P.ghist + ((size_t)(p & 1) * P.batch + row) * kMaxBins;
@@ -295,7 +286,7 @@ __device__ __forceinline__ void slot_masks(const Source& src, const typename Sou
 // Which wave gets which part of the workgroup's range depends on timing: the ORDER of the outputs
 // may differ between runs, the selected set does not.
 template <int DT>
-__device__ __forceinline__ void flush_wave_winners(const ClassifyOut<DT>& o, const uint2* buf, u32* run, u32 fill,
+__device__ __noinline__ void flush_wave_winners(const ClassifyOut<DT>& o, const uint2* buf, u32* run, u32 fill,
                                                    u32 lane) {
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     u32 base = 0;
@@ -312,7 +303,7 @@ __device__ __forceinline__ void flush_wave_winners(const ClassifyOut<DT>& o, con
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
 }
 template <int DT>
-__device__ __forceinline__ void flush_wave_candidates(const ClassifyOut<DT>& o, const uint2* buf, u32* run, u32 fill,
+__device__ __noinline__ void flush_wave_candidates(const ClassifyOut<DT>& o, const uint2* buf, u32* run, u32 fill,
                                                       u32 lane) {
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     u32 base = 0;
@@ -450,23 +441,21 @@ __device__ __forceinline__ void classify_phase(const Source& src, const Params& 
     __syncthreads();
     WriteState ws;
     ws.fillW = ws.fillC = 0;
-    for_each_tile<SINGLE ? 1 : 2>(src, wg, G, ntiles, [&](const typename Source::Tile& cur) {
-        if constexpr (SRC != SRC_RUNTIME) {
-            if (floatcmp && cur.full)
-                classify_tile<true, true, Source, DT, SRC, B>(src, cur, ctx, o, sm, lane, wave, ws);
-            else if (floatcmp)
-                classify_tile<false, true, Source, DT, SRC, B>(src, cur, ctx, o, sm, lane, wave, ws);
-            else if (cur.full)
+    for_each_tile<SINGLE ? 1 : 2>(
+        src, wg, G, ntiles,
+        [&](const typename Source::Tile& cur) {
+            if constexpr (SRC != SRC_RUNTIME) {
+                if (floatcmp)
+                    classify_tile<true, true, Source, DT, SRC, B>(src, cur, ctx, o, sm, lane, wave, ws);
+                else
+                    classify_tile<true, false, Source, DT, SRC, B>(src, cur, ctx, o, sm, lane, wave, ws);
+            } else {
                 classify_tile<true, false, Source, DT, SRC, B>(src, cur, ctx, o, sm, lane, wave, ws);
-            else
-                classify_tile<false, false, Source, DT, SRC, B>(src, cur, ctx, o, sm, lane, wave, ws);
-        } else {
-            if (cur.full)
-                classify_tile<true, false, Source, DT, SRC, B>(src, cur, ctx, o, sm, lane, wave, ws);
-            else
-                classify_tile<false, false, Source, DT, SRC, B>(src, cur, ctx, o, sm, lane, wave, ws);
-        }
-    });
+            }
+        },
+        [&](const typename Source::Tile& cur) {
+            classify_tile<false, false, Source, DT, SRC, B>(src, cur, ctx, o, sm, lane, wave, ws);
+        });
     if (ws.fillW) flush_wave_winners<DT>(o, sm.wbuf[wave], &sm.runW, ws.fillW, lane);
     if (ws.fillC) flush_wave_candidates<DT>(o, sm.cbuf[wave], &sm.runC, ws.fillC, lane);
 }
@@ -611,234 +600,56 @@ __global__ void __launch_bounds__(kRowBlock) k_row(Params P) {
     finish_row<DT>(P, row, st, sm, 1, 3u);
 }
 
-// ------------------------------------------------------------------------------------------------
-// host side
-// ------------------------------------------------------------------------------------------------
-struct Layout {
-    size_t state_off, ghist_off, bases_off, swg_off, cand0_off, cand1_off, total;
-};
-
-static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
-
-struct Config {
-    int d, path, G;
-    u32 small;
-    int npass;
-    u32 idx_max, dirmask;
-    PassInfo pass[kMaxPasses];
-};
-
-static int elem_bytes(rtopk_dtype dt) { return dt == RTOPK_F32 ? 4 : 2; }
-
-static rtopk_status make_config(int64_t batch, int64_t n, int64_t k, rtopk_dtype dt, int largest, uint32_t flags,
-                                const rtopk_tuning* tn, Config* c) {
-    if (batch < 1 || batch > 0x7fffffff || n < 1 || n > RTOPK_MAX_N || k < 1 || k > n) return RTOPK_ERR_INVALID_ARG;
-    if (dt != RTOPK_F32 && dt != RTOPK_F16 && dt != RTOPK_BF16) return RTOPK_ERR_INVALID_ARG;
-    if (flags & ~(uint32_t)RTOPK_FLAG_SCALING) return RTOPK_ERR_INVALID_ARG;
-    int d = dt == RTOPK_F32 ? 12 : 11;
-    int path = 0, G = 0;
-    u32 small = 32768;
-    if (tn) {
-        if (tn->digit_bits) {
-            if (tn->digit_bits < 8 || tn->digit_bits > 12) return RTOPK_ERR_INVALID_ARG;
-            d = tn->digit_bits;
-        }
-        if (tn->path < 0 || tn->path > 2 || tn->wgs_per_row < 0 || tn->small_threshold < 0) return RTOPK_ERR_INVALID_ARG;
-        path = tn->path;
-        G = tn->wgs_per_row;
-        if (tn->small_threshold) small = (u32)tn->small_threshold;
-    }
-    if (path == 0) {
-        // short rows, or enough rows to occupy every compute unit: one workgroup per row
-        path = (n <= (1 << 18) || (batch >= 256 && n <= (1 << 20))) ? 1 : 2;
-        if (batch > 65535) path = 1;
-    }
-    if (path == 2 && batch > 65535) return RTOPK_ERR_INVALID_ARG;  // rows are the grid's y dimension
-    const int eb = elem_bytes(dt);
-    const int64_t tile_elems = (int64_t)kGridBlock * kVecs * 4;  // 16 elements per lane for every type
-    const int64_t ntiles = (n + 16 / eb - 1 + tile_elems) / tile_elems;  // one spare for the lead-in
-    if (path == 2) {
-        if (G == 0) {
-            int64_t want = 512 / batch;  // about two workgroups per compute unit in total
-            if (want < 1) want = 1;
-            G = (int)want;
-        }
-        if (G > ntiles) G = (int)ntiles;
-        if (G > 4096) G = 4096;
-        if (G < 1) G = 1;
-    } else {
-        G = 1;
-    }
-    c->d = d;
-    c->path = path;
-    c->G = G;
-    c->small = small;
-    c->dirmask = largest ? 0u : (dt == RTOPK_F32 ? 0xffffffffu : 0xffff0000u);
-
-    int np = 0;
-    const int kw = dt == RTOPK_F32 ? 32 : 16;
-    if ((flags & RTOPK_FLAG_SCALING) && dt == RTOPK_F32) {
-        for (int hi = 32; hi > 0;) {
-            int bits = d < hi ? d : hi;
-            c->pass[np++] = PassInfo{SRC_SCALED, (u32)(hi - bits), (u32)bits};
-            hi -= bits;
-        }
-    }
-    for (int hi = 32; hi > 32 - kw;) {
-        int bits = d < hi - (32 - kw) ? d : hi - (32 - kw);
-        c->pass[np++] = PassInfo{SRC_KEY, (u32)(hi - bits), (u32)bits};
-        hi -= bits;
-    }
-    int ib = 0;
-    while (((int64_t)1 << ib) < n) ++ib;
-    c->idx_max = ib == 0 ? 0u : (u32)(((u64)1 << ib) - 1);
-    for (int hi = ib; hi > 0;) {
-        int bits = d < hi ? d : hi;
-        c->pass[np++] = PassInfo{SRC_IDX, (u32)(hi - bits), (u32)bits};
-        hi -= bits;
-    }
-    if (np > kMaxPasses) return RTOPK_ERR_INVALID_ARG;
-    c->npass = np;
-    return RTOPK_OK;
-}
-
-static Layout make_layout(int64_t batch, int64_t n, const Config& c) {
-    Layout L;
-    size_t off = 0;
-    L.state_off = off;
-    off = align_up(off + (size_t)batch * RTOPK_TRACE_STRIDE, 256);
-    L.ghist_off = off;
-    off = align_up(off + (size_t)2 * batch * kMaxBins * 4, 256);
-    L.bases_off = off;
-    off = align_up(off + (size_t)batch * c.G * 2 * 4, 256);
-    L.swg_off = off;
-    off = align_up(off + (size_t)batch * c.G * kSwgStride * 4, 256);
-    L.cand0_off = off;
-    off = align_up(off + (size_t)batch * (size_t)n * 8, 256);
-    L.cand1_off = off;
-    off = align_up(off + (size_t)batch * (size_t)n * 8, 256);
-    L.total = off + 256;  // the last 16-byte load of an odd-length candidate array may touch 8 bytes past it
-    return L;
+static void mark(void* const* events, int i, hipStream_t st) {
+    if (events && events[i]) (void)hipEventRecord((hipEvent_t)events[i], st);
 }
 
 template <int DT>
-static rtopk_status launch_all(const Params& P, const Config& c, bool scaled, hipStream_t st) {
+static rtopk_status launch_all(const Params& P, const Config& c, bool scaled, hipStream_t st, void* const* events) {
     const int batch = P.batch;
+    mark(events, 0, st);
+    constexpr int kScaledSrc = DT == RTOPK_F32 ? SRC_SCALED : SRC_KEY;  // 16-bit keys are never scaled
+    if (DT != RTOPK_F32) scaled = false;
     if (c.path == 1) {
+        mark(events, 1, st);
+        mark(events, 2, st);
+        mark(events, 3, st);
         if (scaled)
-            hipLaunchKernelGGL((k_row<DT, SRC_SCALED>), dim3(batch), dim3(kRowBlock), 0, st, P);
+            hipLaunchKernelGGL((k_row<DT, kScaledSrc>), dim3(batch), dim3(kRowBlock), 0, st, P);
         else
             hipLaunchKernelGGL((k_row<DT, SRC_KEY>), dim3(batch), dim3(kRowBlock), 0, st, P);
+        mark(events, 4, st);
         return hipGetLastError() == hipSuccess ? RTOPK_OK : RTOPK_ERR_HIP;
     }
     const dim3 grid(c.G, batch), block(kGridBlock);
     hipLaunchKernelGGL((k_init<DT>), dim3(batch), dim3(256), 0, st, P);
+    mark(events, 1, st);
     const bool nt = (P.flags & kInternalStream) != 0;
     if (scaled && nt) {
-        hipLaunchKernelGGL((k_hist_keys<DT, SRC_SCALED, true>), grid, block, 0, st, P);
-        hipLaunchKernelGGL((k_classify_keys<DT, SRC_SCALED, true>), grid, block, 0, st, P);
+        hipLaunchKernelGGL((k_hist_keys<DT, kScaledSrc, true>), grid, block, 0, st, P);
+        mark(events, 2, st);
+        hipLaunchKernelGGL((k_classify_keys<DT, kScaledSrc, true>), grid, block, 0, st, P);
     } else if (scaled) {
-        hipLaunchKernelGGL((k_hist_keys<DT, SRC_SCALED, false>), grid, block, 0, st, P);
-        hipLaunchKernelGGL((k_classify_keys<DT, SRC_SCALED, false>), grid, block, 0, st, P);
+        hipLaunchKernelGGL((k_hist_keys<DT, kScaledSrc, false>), grid, block, 0, st, P);
+        mark(events, 2, st);
+        hipLaunchKernelGGL((k_classify_keys<DT, kScaledSrc, false>), grid, block, 0, st, P);
     } else if (nt) {
         hipLaunchKernelGGL((k_hist_keys<DT, SRC_KEY, true>), grid, block, 0, st, P);
+        mark(events, 2, st);
         hipLaunchKernelGGL((k_classify_keys<DT, SRC_KEY, true>), grid, block, 0, st, P);
     } else {
         hipLaunchKernelGGL((k_hist_keys<DT, SRC_KEY, false>), grid, block, 0, st, P);
+        mark(events, 2, st);
         hipLaunchKernelGGL((k_classify_keys<DT, SRC_KEY, false>), grid, block, 0, st, P);
     }
+    mark(events, 3, st);
     for (int p = 1; p < c.npass; ++p) {
         hipLaunchKernelGGL((k_hist_cand<DT>), grid, block, 0, st, P, p);
         hipLaunchKernelGGL((k_classify_cand<DT>), grid, block, 0, st, P, p);
     }
     hipLaunchKernelGGL((k_finish<DT>), dim3(batch), dim3(kRowBlock), 0, st, P);
+    mark(events, 4, st);
     return hipGetLastError() == hipSuccess ? RTOPK_OK : RTOPK_ERR_HIP;
 }
 
 }  // namespace rtopk
-
-using namespace rtopk;
-
-extern "C" {
-
-const char* rtopk_status_string(rtopk_status s) {
-    switch (s) {
-        case RTOPK_OK: return "ok";
-        case RTOPK_ERR_INVALID_ARG: return "invalid argument";
-        case RTOPK_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
-        case RTOPK_ERR_UNSUPPORTED: return "unsupported (misaligned buffer)";
-        case RTOPK_ERR_HIP: return "HIP runtime rejected a launch";
-    }
-    return "unknown status";
-}
-
-const char* rtopk_version(void) { return "0.1"; }
-
-rtopk_status rtopk_workspace_bytes(int64_t batch, int64_t n, int64_t k, rtopk_dtype dt, uint32_t flags,
-                                   const rtopk_tuning* tuning, size_t* bytes_out) {
-    if (!bytes_out) return RTOPK_ERR_INVALID_ARG;
-    Config c;
-    rtopk_status s = make_config(batch, n, k, dt, 1, flags, tuning, &c);
-    if (s != RTOPK_OK) return s;
-    *bytes_out = make_layout(batch, n, c).total;
-    return RTOPK_OK;
-}
-
-rtopk_status rtopk_select_ex(const void* keys, int64_t batch, int64_t n, int64_t k, rtopk_dtype dt, int largest,
-                             uint32_t flags, uint64_t seed, void* out_values, int64_t* out_indices, void* workspace,
-                             size_t workspace_bytes, void* hip_stream, const rtopk_tuning* tuning) {
-    if (!keys || !out_values || !out_indices || !workspace) return RTOPK_ERR_INVALID_ARG;
-    Config c;
-    rtopk_status s = make_config(batch, n, k, dt, largest, flags, tuning, &c);
-    if (s != RTOPK_OK) return s;
-    const int eb = elem_bytes(dt);
-    if (((uintptr_t)keys % eb) || ((uintptr_t)out_values % eb) || ((uintptr_t)out_indices % 8) ||
-        ((uintptr_t)workspace % 256))
-        return RTOPK_ERR_UNSUPPORTED;
-    const Layout L = make_layout(batch, n, c);
-    if (workspace_bytes < L.total) return RTOPK_ERR_WORKSPACE_TOO_SMALL;
-
-    Params P;
-    memset(&P, 0, sizeof(P));
-    char* ws = (char*)workspace;
-    P.keys = keys;
-    P.out_values = out_values;
-    P.out_indices = (long long*)out_indices;
-    P.state = (rtopk_row_trace*)(ws + L.state_off);
-    P.ghist = (u32*)(ws + L.ghist_off);
-    P.bases = (u32*)(ws + L.bases_off);
-    P.swg = (u32*)(ws + L.swg_off);
-    P.cand[0] = (uint2*)(ws + L.cand0_off);
-    P.cand[1] = (uint2*)(ws + L.cand1_off);
-    P.n = n;
-    P.k = k;
-    P.batch = (int)batch;
-    P.G = c.G;
-    P.dirmask = c.dirmask;
-    P.idx_max = c.idx_max;
-    P.small = c.small;
-    P.npass = c.npass;
-    P.flags = flags;
-    // two sweeps over more data than the 256 MB last-level cache holds: stream it past the caches
-    if ((size_t)batch * (size_t)n * (size_t)eb > ((size_t)384 << 20)) P.flags |= kInternalStream;
-    P.seed = seed;
-    for (int i = 0; i < c.npass; ++i) P.pass[i] = c.pass[i];
-
-    hipStream_t st = (hipStream_t)hip_stream;
-    const bool scaled = (flags & RTOPK_FLAG_SCALING) && dt == RTOPK_F32;
-    switch (dt) {
-        case RTOPK_F32: return launch_all<RTOPK_F32>(P, c, scaled, st);
-        case RTOPK_F16: return launch_all<RTOPK_F16>(P, c, false, st);
-        case RTOPK_BF16: return launch_all<RTOPK_BF16>(P, c, false, st);
-    }
-    return RTOPK_ERR_INVALID_ARG;
-}
-
-rtopk_status rtopk_select(const void* keys, int64_t batch, int64_t n, int64_t k, rtopk_dtype dt, int largest,
-                          uint32_t flags, uint64_t seed, void* out_values, int64_t* out_indices, void* workspace,
-                          size_t workspace_bytes, void* hip_stream) {
-    return rtopk_select_ex(keys, batch, n, k, dt, largest, flags, seed, out_values, out_indices, workspace,
-                           workspace_bytes, hip_stream, nullptr);
-}
-
-}  // extern "C"

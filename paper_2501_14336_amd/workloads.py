@@ -125,7 +125,8 @@ def narrow(n: int, seed: int, dtype=np.float32) -> np.ndarray:
     """uniform in [1, 1 + 2^-12): 2048 distinct fp32 values; a single fp16 value (1.0)."""
     out = np.empty(n, dtype=dtype)
     for s, m in _chunks(n):
-        out[s:s + m] = (1.0 + _u01(s, m, seed, 0) * 2.0 ** -12).astype(np.float32).astype(dtype)
+        j = np.floor(_u01(s, m, seed, 0) * 2048.0)          # the 2048 fp32 values of the range, equally likely
+        out[s:s + m] = (1.0 + j * 2.0 ** -23).astype(np.float32).astype(dtype)
     return out
 
 

@@ -1,0 +1,280 @@
+"""GPU parity tests: the HIP path, called through the C-ABI binding, against the CPU oracle.
+
+Bar: bit-exact.  For every row the index SET equals the oracle's (lowest-index-first ties), every output
+value is the input's bit pattern at its index, and the sorted value words equal the oracle's.  The order of
+outputs inside a row is unspecified at the boundary, so comparisons are made on sets.
+
+Small and medium cases are compared element by element with the sort oracle; they span several 8192-element
+tiles, ragged tails, misaligned rows and every code path (one workgroup per row, many workgroups per row,
+single-workgroup finish, every digit width, scaling on and off).  The full-size configurations are compared
+with the oracle where a full sort finishes in seconds and otherwise checked with the O(n) property test in
+tests/verify.py, which decides from the definition alone whether an answer is THE top-k.
+"""
+import sys
+
+import numpy as np
+import pytest
+
+import oracle
+from oracle import radix_ref as R
+from paper_2501_14336_amd import workloads as W
+from tests import verify
+from tests.gpu_util import BF16, F16, F32, gpu_topk, to_device
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+def _check_rows(bits2d, dtype, k, largest, gv, gi, traces, rows=None):
+    rows = range(bits2d.shape[0]) if rows is None else rows
+    for r in rows:
+        assert traces[r].error == 0, "device error flag %d in row %d" % (traces[r].error, r)
+        assert traces[r].done, "row %d did not finish" % r
+        wv, wi = oracle.topk(bits2d[r], dtype, k, largest)
+        verify.assert_same_selection(bits2d[r], gv[r], gi[r], wv[0], wi[0])
+
+
+def _run_and_check(name, bits, dtype, k, largest=True, scaling=False, seed=0, tuning=None):
+    _say("case:", name, "shape", bits.shape, "k", k, "largest", largest, "scaling", scaling, "tuning", tuning)
+    x = to_device(bits, dtype)
+    gv, gi, tr, _ = gpu_topk(x, dtype, k, largest, scaling, seed, tuning)
+    b2 = bits.reshape(1, -1) if bits.ndim == 1 else bits
+    _check_rows(b2, dtype, k, largest, gv, gi, tr)
+    return tr
+
+
+# ------------------------------------------------------------------------------------------------ small / medium
+
+SIZES = [1, 2, 63, 64, 65, 1000, 8191, 8192, 8193, 40000, 100003]
+
+
+@pytest.mark.parametrize("path", [1, 2])
+@pytest.mark.parametrize("n", SIZES)
+def test_fp32_normal_all_sizes_both_paths(path, n):
+    bits = W.normal(n, seed=n).view(np.uint32)
+    for k in sorted({1, min(n, 7), max(1, n // 2), n}):
+        for largest in (True, False):
+            _run_and_check("normal", bits, F32, k, largest, tuning=dict(path=path))
+
+
+@pytest.mark.parametrize("path", [1, 2])
+def test_duplicates_ties_at_kth_key(path):
+    bits = W.duplicates(50000, seed=1).view(np.uint32)
+    for k in (10, 30000, 49000):
+        _run_and_check("dup", bits, F32, k, True, tuning=dict(path=path))
+        # force the many-workgroup kernels through every pass, including the index (tie-break) digits
+        _run_and_check("dup multi", bits, F32, k, True, tuning=dict(path=path, small_threshold=1, wgs_per_row=7))
+        _run_and_check("dup smallest", bits, F32, k, False, tuning=dict(path=path, small_threshold=1, wgs_per_row=3))
+
+
+@pytest.mark.parametrize("path", [1, 2])
+@pytest.mark.parametrize("d", [8, 11, 12])
+def test_special_values_every_digit_width(path, d):
+    bits = W.specials_ramp(30001, seed=2, with_nan=True).view(np.uint32)
+    for k in (5, 1000, 20000):            # k = 5 lies inside the NaN class
+        for largest in (True, False):
+            _run_and_check("specials", bits, F32, k, largest, tuning=dict(path=path, digit_bits=d))
+
+
+@pytest.mark.parametrize("path", [1, 2])
+def test_zero_boundary_and_signed_zero_ties(path):
+    # many +0 and -0: the k-th key falls on the boundary where a float comparison cannot replace the key
+    n = 70001
+    x = W.uniform_range(n, 11, -1e6, 1e6)
+    x[::7] = 0.0
+    x[3::7] = -0.0
+    npos = int((x > 0).sum())
+    for dtype, bits in ((F32, x.view(np.uint32)), (F16, x.astype(np.float16).view(np.uint16)),
+                        (BF16, W.to_bf16_bits(x))):
+        for k in (npos, npos + 5, npos + n // 7 + 3, n // 2):
+            for largest in (True, False):
+                _run_and_check("zero boundary", bits, dtype, k, largest, tuning=dict(path=path))
+
+
+@pytest.mark.parametrize("path", [1, 2])
+def test_scaling_is_result_neutral(path):
+    for bits in (W.specials_ramp(30001, seed=3, with_nan=True).view(np.uint32),
+                 W.narrow(60000, seed=4).view(np.uint32),
+                 W.uniform_range(60000, 5, 128.6, 128.7).view(np.uint32),
+                 W.duplicates(60000, seed=6).view(np.uint32)):
+        for k in (1, 512, 30000):
+            for largest in (True, False):
+                for seed in (0, 12345):
+                    _run_and_check("scaled", bits, F32, k, largest, scaling=True, seed=seed, tuning=dict(path=path))
+
+
+@pytest.mark.parametrize("dtype", [F16, BF16])
+@pytest.mark.parametrize("path", [1, 2])
+def test_16bit_types(dtype, path):
+    n = 50001
+    if dtype == F16:
+        data = [W.normal(n, 7).astype(np.float16).view(np.uint16),
+                W.specials_ramp(n, 8, dtype=np.float16, with_nan=True).view(np.uint16),
+                W.narrow(n, 9, dtype=np.float16).view(np.uint16)]          # every key equal: ties only
+    else:
+        data = [W.llm_logits(1, n, 10)[0], W.to_bf16_bits(W.specials_ramp(n, 11, with_nan=True))]
+    for bits in data:
+        for k in (1, 50, 8192, n):
+            for largest in (True, False):
+                _run_and_check("16-bit", bits, dtype, k, largest, tuning=dict(path=path))
+        _run_and_check("16-bit scaling flag ignored", bits, dtype, 100, True, scaling=True, tuning=dict(path=path))
+
+
+@pytest.mark.parametrize("path", [1, 2])
+def test_batch_with_misaligned_rows(path):
+    # odd row lengths: only row 0 starts on a 16-byte boundary
+    for dtype, bits in ((BF16, W.llm_logits(9, 4099, 12)), (F32, W.normal(9 * 10007, 13).view(np.uint32).reshape(9, 10007)),
+                        (F16, W.normal(5 * 8195, 14).astype(np.float16).view(np.uint16).reshape(5, 8195))):
+        for k in (1, 50, 2000):
+            _run_and_check("batch misaligned", bits, dtype, k, True, tuning=dict(path=path))
+            _run_and_check("batch misaligned", bits, dtype, k, False, tuning=dict(path=path, wgs_per_row=3))
+
+
+def test_batch_many_rows_grid_path():
+    bits = W.normal(64 * 20000, 15).view(np.uint32).reshape(64, 20000)
+    _run_and_check("batch 64 grid", bits, F32, 333, True, tuning=dict(path=2, small_threshold=16))
+
+
+def test_closed_forms_on_gpu():
+    n, k = 100000, 777
+    desc = np.linspace(5.0, -5.0, n).astype(np.float32)
+    for path in (1, 2):
+        x = to_device(desc.view(np.uint32), F32)
+        _, gi, _, _ = gpu_topk(x, F32, k, True, tuning=dict(path=path))
+        assert np.array_equal(np.sort(gi[0]), np.arange(k))                      # descending input: first k
+        _, gi, _, _ = gpu_topk(x, F32, k, False, tuning=dict(path=path))
+        assert np.array_equal(np.sort(gi[0]), np.arange(n - k, n))
+        eq = np.full(n, 0.999, dtype=np.float32)
+        _, gi, _, _ = gpu_topk(to_device(eq.view(np.uint32), F32), F32, k, True, tuning=dict(path=path))
+        assert np.array_equal(np.sort(gi[0]), np.arange(k))                      # all equal: lowest indices
+        _, gi, _, _ = gpu_topk(to_device(eq.view(np.uint32), F32), F32, n, True, tuning=dict(path=path))
+        assert np.array_equal(np.sort(gi[0]), np.arange(n))                      # k = n: everything
+
+
+def test_same_set_for_every_tuning_and_repeated_runs():
+    bits = W.uniform_range(300000, 16, -1e6, 1e6).view(np.uint32)
+    k = 20000
+    x = to_device(bits, F32)
+    want = None
+    for tuning in (None, dict(path=1), dict(path=2), dict(path=2, wgs_per_row=1), dict(path=2, wgs_per_row=37),
+                   dict(path=2, digit_bits=8, small_threshold=1), dict(digit_bits=11), dict(path=2, small_threshold=100000)):
+        for rep in range(3):
+            _say("tuning", tuning, "rep", rep)
+            gv, gi, tr, _ = gpu_topk(x, F32, k, True, tuning=tuning)
+            got = np.sort(gi[0])
+            if want is None:
+                _check_rows(bits.reshape(1, -1), F32, k, True, gv, gi, tr)
+                want = got
+            assert np.array_equal(got, want)
+
+
+def test_pass_records_match_algorithm_1_model():
+    # the chosen bin, the pivot's rank in it and the candidate count of every key-digit pass equal what the
+    # step-by-step numpy model of Algorithm 1 computes (oracle/radix_ref.py)
+    bits = W.normal(200000, 17).view(np.uint32)
+    for d in (8, 12):
+        for largest in (True, False):
+            ref = R.radix_topk(bits, F32, 5000, d=d, largest=largest)
+            for tuning in (dict(path=1, digit_bits=d), dict(path=2, digit_bits=d, small_threshold=1)):
+                tr = _run_and_check("trace", bits, F32, 5000, largest, tuning=tuning)[0]
+                out = 0
+                for j, rec in enumerate(tr.passes):
+                    if rec.source != 1:                 # index digits: tie break, not part of Algorithm 1
+                        break
+                    want = ref.passes[j]
+                    assert (rec.shift, rec.shift + rec.bits) == (want.low, want.high)
+                    assert rec.bin == want.bin
+                    assert rec.out_before == out
+                    if rec.cand_after:
+                        assert rec.k_after == want.k_after and rec.cand_after == want.candidates_after
+                    else:                                # whole bin taken: the model's pivot rank equals the bin size
+                        assert want.k_after == want.candidates_after
+                    out += rec.winners
+                assert tr.passes[-1].out_before + tr.passes[-1].winners == 5000
+
+
+def test_scaling_spreads_adversarial_range_on_gpu():
+    # Section 5.5's case: every key of U[128.6, 128.7] shares its top 12 bits; with scaling the first pass
+    # already discards most keys
+    n = 1 << 20
+    bits = W.uniform_range(n, 18, 128.6, 128.7).view(np.uint32)
+    plain = _run_and_check("adversarial plain", bits, F32, 512, True, tuning=dict(path=2))[0]
+    scaled = _run_and_check("adversarial scaled", bits, F32, 512, True, scaling=True, tuning=dict(path=2))[0]
+    assert plain.passes[0].cand_after == n
+    assert scaled.passes[0].source == 0 and scaled.passes[0].cand_after < n // 4
+    assert scaled.a_s != 0.0
+
+
+# ------------------------------------------------------------------------------------------------ full sizes
+
+def test_config1_full():
+    bits = W.config1().view(np.uint32)
+    _run_and_check("config 1", bits, F32, 32, True)
+
+
+def test_config2_full_k_sweep_both_directions():
+    x = W.config2()
+    bits = x.view(np.uint32)
+    xd = to_device(bits, F32)
+    ws = None
+    for largest in (True, False):
+        _say("config 2: oracle sort, largest =", largest)
+        order = oracle.sort_row(bits, F32, largest)
+        for k in (16, 256, 4096, 65536, 1 << 20):
+            _say("config 2 k", k)
+            gv, gi, tr, ws = gpu_topk(xd, F32, k, largest, workspace=ws)
+            assert tr[0].error == 0 and tr[0].done
+            verify.assert_same_selection(bits, gv[0], gi[0], bits[order[:k]], order[:k])
+
+
+def test_config3_full_batch_bf16():
+    _say("config 3: generating 1024 x 131072 bf16")
+    bits = W.config3()
+    xd = to_device(bits, BF16)
+    ws = None
+    sample_rows = list(range(0, 1024, 97))
+    for k in (50, 1024, 8192):
+        _say("config 3 k", k)
+        gv, gi, tr, ws = gpu_topk(xd, BF16, k, True, workspace=ws)
+        _check_rows(bits, BF16, k, True, gv, gi, tr, rows=sample_rows)           # sort oracle on sampled rows
+        for r in range(1024):                                                     # definition check on every row
+            assert tr[r].error == 0 and tr[r].done
+            verify.check_topk_properties(bits[r], BF16, k, True, gv[r], gi[r])
+
+
+def test_config4_full_large_k():
+    _say("config 4: generating 2^28 fp32")
+    x = W.config4()
+    bits = x.view(np.uint32)
+    xd = to_device(bits, F32)
+    ws = None
+    for k in (1 << 20, 1 << 24, 1 << 27):
+        _say("config 4 k", k)
+        gv, gi, tr, ws = gpu_topk(xd, F32, k, True, workspace=ws)
+        assert tr[0].error == 0 and tr[0].done
+        verify.check_topk_properties(bits, F32, k, True, gv[0], gi[0])
+
+
+@pytest.mark.parametrize("case", ["a", "b", "c"])
+@pytest.mark.parametrize("dt", [np.float32, np.float16])
+def test_config5_full_adversarial(case, dt):
+    _say("config 5", case, dt.__name__, ": generating 2^26")
+    x = W.config5(case, dtype=dt)
+    dtype = F32 if dt == np.float32 else F16
+    bits = verify.as_bits(x, dtype)
+    xd = to_device(bits, dtype)
+    k = 1 << 16
+    ws = None
+    for largest in (True, False):
+        for scaling in ((False, True) if dtype == F32 else (False,)):
+            _say("config 5", case, "largest", largest, "scaling", scaling)
+            gv, gi, tr, ws = gpu_topk(xd, dtype, k, largest, scaling=scaling, seed=77, workspace=ws)
+            assert tr[0].error == 0 and tr[0].done
+            verify.check_topk_properties(bits, dtype, k, largest, gv[0], gi[0])
+    if case == "a" and dtype == F16:
+        # every fp16 key equals 1.0: the answer is the first k indices
+        assert np.array_equal(np.sort(gi[0]), np.arange(k))
