@@ -34,6 +34,9 @@ def main() -> int:
     ap.add_argument("--log2k", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-batch-case", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain device copy of the input (n*4 bytes read, n*4 written), so that a "
+                         "counter run contains a kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not supported"
@@ -68,6 +71,12 @@ def main() -> int:
             e.record(stream)  # instantiates the underlying hipEvent_t
             evs.append(e)
         return evs
+
+    if args.calibration_copy:
+        y = torch.empty_like(x)
+        y.copy_(x)
+        torch.cuda.synchronize()
+        del y
 
     for _ in range(warmup):
         B.topk(x, k, True, workspace=ws, out=(vals, idx))

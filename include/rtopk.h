@@ -20,7 +20,7 @@
  *
  * The selected SET is unique and reproducible.  The order of the k outputs
  * inside a row is unspecified (the paper's output is unsorted, Section 2.3.1);
- * it is, however, the same on every run with the same arguments.
+ * the order may differ between runs with the same arguments (the set never does).
  */
 #ifndef RTOPK_H
 #define RTOPK_H
