@@ -31,9 +31,9 @@ struct Params {
     void* out_values;        // Y values, [batch][k]
     long long* out_indices;  // Y indices, [batch][k]
     rtopk_row_trace* state;  // per-row loop state + trace, stride RTOPK_TRACE_STRIDE bytes
-    u32* ghist;              // [2][batch][kMaxBins]  global histogram, one buffer per pass parity
-    u32* bases;              // [batch][G][2]       per-workgroup output / candidate write offsets
-    u32* swg;                // [batch][G][kSwgStride]  per-workgroup suffix sums of its local histogram
+    u32* ghist;              // [3][batch][kMaxBins]  global histograms; pass p reads buffer p % 3, fills (p+1) % 3, clears (p+2) % 3
+    u32* seg;                // [2][batch][G][2]    (start, count) of the candidates each workgroup wrote, per pass parity
+    u32* swg;                // [2][batch][G][kSwgStride]  per-workgroup suffix sums of its local histogram, per pass parity
     uint2* cand[2];          // [batch][n]          (raw bits, index) candidates, ping-pong
     long long n, k;
     int batch, G;
@@ -289,7 +289,8 @@ struct KeySource {
     }
 };
 
-// A candidate array of (raw bits, index) pairs, two per vector.
+// A segment [start, start + count) of a candidate array of (raw bits, index) pairs, two per 16-byte vector.
+// Loads start at the even entry at or before `start`; the lead-in entry is masked.
 template <int B, int V>
 struct CandSource {
     static constexpr int E = 2;
@@ -297,19 +298,22 @@ struct CandSource {
     static constexpr int kTileVecs = B * V;
     typedef TileRegs<V> Tile;
 
-    const uint4* base;
+    const uint4* base;  // vector holding entry `start`
+    u32 lead;           // 1 if `start` is odd
     u32 count;
     u64 nvec;
 
-    __device__ __forceinline__ void init(const uint2* c, u32 count_) {
-        base = (const uint4*)c;
+    __device__ __forceinline__ void init(const uint2* c, u32 start, u32 count_) {
+        lead = start & 1u;
+        base = (const uint4*)(c + (start - lead));
         count = count_;
-        nvec = ((u64)count_ + 1) / 2;
+        nvec = ((u64)lead + (u64)count_ + 1) / 2;
     }
     __device__ __forceinline__ u32 ntiles() const { return (u32)((nvec + kTileVecs - 1) / kTileVecs); }
     __device__ __forceinline__ void full_range(u32& f0, u32& f1) const {
-        f0 = 0;
-        f1 = (u32)((u64)count / ((u64)kTileVecs * E));
+        f0 = lead;
+        f1 = (u32)(((u64)lead + (u64)count) / ((u64)kTileVecs * E));
+        if (f1 < f0) f1 = f0;
     }
     __device__ __forceinline__ void load_full(u32 tile, u32 tid, Tile& t) const {
         const u64 v0 = (u64)tile * kTileVecs;
@@ -321,7 +325,7 @@ struct CandSource {
     __device__ __forceinline__ void load(u32 tile, u32 tid, Tile& t) const {
         u64 v0 = (u64)tile * kTileVecs;
         t.tile = tile;
-        t.full = (v0 + kTileVecs) * E <= (u64)count;
+        t.full = (tile != 0 || lead == 0) && ((v0 + kTileVecs) * E <= (u64)lead + (u64)count);
 #pragma unroll
         for (int u = 0; u < V; ++u) {
             u64 v = v0 + (u64)u * B + tid;
@@ -339,7 +343,9 @@ struct CandSource {
     }
     __device__ __forceinline__ void get(const Tile& t, int s, u32& raw, u32& idx, bool& valid) const {
         const int u = s / E, j = s % E;
-        valid = t.full || ((t.tile * (u32)kTileVecs + (u32)(u * B) + threadIdx.x) * (u32)E + (u32)j) < count;
+        // position inside the segment; the lead-in wraps to a huge value
+        const u32 pos = (t.tile * (u32)kTileVecs + (u32)(u * B) + threadIdx.x) * (u32)E + (u32)j - lead;
+        valid = t.full || pos < count;
         raw = j ? t.r[u].z : t.r[u].x;
         idx = j ? t.r[u].w : t.r[u].y;
     }

@@ -1,6 +1,7 @@
 // Radix top-k kernels for gfx950 (templates; instantiated once per key type by rtopk_f32/f16/bf16.hip).
 //
-// One digit pass (paper Section 2.3.1) is two sweeps over the current candidates:
+// The first digit pass (paper Section 2.3.1) is two sweeps over the input; every later pass is one sweep
+// over the candidates, because CLASSIFY also counts the NEXT digit of what it keeps:
 //
 //   HIST      countBin + selectBin.  Every workgroup builds a local histogram of the pass's digit in LDS
 //             (hierarchical atomics, Section 3.1.1), adds it to the row's global histogram, and stores the
@@ -10,6 +11,11 @@
 //   CLASSIFY  selectCandidate fused with the filter.  digit > b: the element is certainly in the top k and
 //             goes straight to the output (value bits + int64 index).  digit == b: it stays a candidate and
 //             is appended, with its index, to the next candidate array.  digit < b: dropped.
+//
+//   While it appends a candidate, CLASSIFY adds that candidate's next digit to a fresh LDS histogram; at its
+//   end it publishes the histogram (global atomics) and its suffix sums exactly as HIST does.  The next pass's
+//   workgroup w then reads the segment of the candidate array that workgroup w wrote, so its per-workgroup
+//   counts are already known and no separate histogram sweep over the candidates is needed.
 //
 // Passes walk the digits of the key from the most significant one down and then the digits of
 // (idx_max - index), which makes every element's extended key unique: the loop ends when the chosen
@@ -193,7 +199,7 @@ __device__ __forceinline__ void hist_phase(const Source& src, const Params& P, i
         });
     __syncthreads();
     if (!SINGLE) {
-        u32* ghist = P.ghist + ((size_t)(p & 1) * P.batch + row) * kMaxBins;
+        u32* ghist = P.ghist + ((size_t)(p % 3) * P.batch + row) * kMaxBins;
         for (int j = tid; j < nb; j += B) {
             u32 c = sm.hist[j];
             if (c) atomicAdd(&ghist[j], c);
@@ -201,7 +207,7 @@ __device__ __forceinline__ void hist_phase(const Source& src, const Params& P, i
     }
     suffix_sums_in_place<B>(sm.hist, nb, sm.wsum);
     if (!SINGLE) {
-        u32* mine = P.swg + ((size_t)row * P.G + wg) * kSwgStride;
+        u32* mine = P.swg + (((size_t)(p & 1) * P.batch + row) * P.G + wg) * kSwgStride;
         for (int j = tid; j < nb; j += B) mine[j] = sm.hist[j];
         if (tid == 0) mine[nb] = 0;
     }
@@ -302,16 +308,27 @@ __device__ __noinline__ void flush_wave_winners(const ClassifyOut<DT>& o, const 
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
 }
+// What the candidate flush needs to count the next pass's digit (countBin of pass p + 1 happens here, on
+// full waves, rather than element by element in the sweep).
+struct NextCount {
+    u32* hist;        // LDS histogram of the next digit, or nullptr when there is no next pass
+    PassInfo pi;
+    u32 dirmask, idx_max;
+    float a_s;
+};
+
 template <int DT>
 __device__ __noinline__ void flush_wave_candidates(const ClassifyOut<DT>& o, const uint2* buf, u32* run, u32 fill,
-                                                      u32 lane) {
+                                                   u32 lane, const NextCount& nc) {
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     u32 base = 0;
     if (lane == 0) base = atomicAdd(run, fill);
     base = __builtin_amdgcn_readfirstlane(base);
     for (u32 i = lane; i < fill; i += 64) {
+        const uint2 e = buf[i];
         const u32 pos = base + i;
-        if (pos < o.ncap) o.cand_out[pos] = buf[i];
+        if (pos < o.ncap) o.cand_out[pos] = e;
+        if (nc.hist) hist_add(nc.hist, digit_of<DT, SRC_RUNTIME>(nc.pi, e.x, e.y, nc.dirmask, nc.idx_max, nc.a_s), lane);
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
 }
@@ -325,7 +342,7 @@ struct WriteState {
 template <bool FULL, bool FLOATCMP, class Source, int DT, int SRC, int B>
 __device__ __forceinline__ void classify_tile(const Source& src, const typename Source::Tile& t, const DigitCtx& c,
                                               const ClassifyOut<DT>& o, Shared<B>& sm, u32 lane, u32 wave,
-                                              WriteState& ws) {
+                                              WriteState& ws, const NextCount& nc) {
     constexpr int E = Source::E;
     constexpr int S = Source::kSlots;
     uint2* wbuf = sm.wbuf[wave];
@@ -351,7 +368,7 @@ __device__ __forceinline__ void classify_tile(const Source& src, const typename 
                 if (mc & me_bit) cbuf[ws.fillC + mbcnt64(mc)] = make_uint2(raw, idx);
                 ws.fillC += (u32)__popcll(mc);
                 if (ws.fillC > (u32)(kStageCap - 64)) {
-                    flush_wave_candidates<DT>(o, cbuf, &sm.runC, ws.fillC, lane);
+                    flush_wave_candidates<DT>(o, cbuf, &sm.runC, ws.fillC, lane, nc);
                     ws.fillC = 0;
                 }
             }
@@ -359,9 +376,16 @@ __device__ __forceinline__ void classify_tile(const Source& src, const typename 
     }
 }
 
+// Where the histogram of the pass comes from.
+enum { HIST_IN_LDS = 0, HIST_IN_GLOBAL = 1 };
+
+// SINGLE: the row is handled by this workgroup alone (wg = 0, G = 1); suffix sums of the pass's histogram are
+// in LDS (HIST_IN_LDS) or the histogram is in the row's global buffer (HIST_IN_GLOBAL, first pass of k_finish).
+// Otherwise G workgroups share the row and the histogram is always global.
 template <class Source, int DT, int SRC, int B, bool SINGLE>
 __device__ __forceinline__ void classify_phase(const Source& src, const Params& P, int p, int row, u32 wg, u32 G,
-                                               const PassEntry& e, rtopk_row_trace* st, Shared<B>& sm, u32 where) {
+                                               const PassEntry& e, rtopk_row_trace* st, Shared<B>& sm, u32 where,
+                                               int hist_from, u32 records, bool own_segment) {
     const DigitCtx ctx = make_digit_ctx(P, p, st->a_s);
     const int nb = 1 << ctx.pi.bits;
     const u32 tid = threadIdx.x;
@@ -369,21 +393,21 @@ __device__ __forceinline__ void classify_phase(const Source& src, const Params& 
     const u32 wave = tid >> 6;
     const u32 ntiles = src.ntiles();
 
-
-    u32 runW = e.out_before, runC = 0;
-    if (!SINGLE) {
+    u32 runW = e.out_before, runC = 0, myC = 0;
+    if (hist_from == HIST_IN_GLOBAL) {
         // every workgroup repeats selectBin on the row's global histogram (cheap, and it spares a
-        // grid-wide hand-off), then sums the counts of the workgroups before it
-        const u32* ghist = P.ghist + ((size_t)(p & 1) * P.batch + row) * kMaxBins;
+        // grid-wide hand-off)
+        const u32* ghist = P.ghist + ((size_t)(p % 3) * P.batch + row) * kMaxBins;
         for (int j = tid; j < nb; j += B) sm.hist[j] = ghist[j];
         __syncthreads();
         suffix_sums_in_place<B>(sm.hist, nb, sm.wsum);
     }
     const Selection sel = select_on_suffix_sums<B>(sm.hist, nb, e.k_rem, &sm.sel, st);
     if (!SINGLE) {
-        const u32 active = ntiles < G ? ntiles : G;
-        const u32 upto = wg < active ? wg : active;
-        const u32* swg_row = P.swg + (size_t)row * P.G * kSwgStride;
+        // exact write offsets: sum, at the chosen bin, the stored suffix sums of the workgroups before this one
+        // (`records` workgroups have a record for this pass)
+        const u32 upto = wg < records ? wg : records;
+        const u32* swg_row = P.swg + ((size_t)(p & 1) * P.batch + row) * P.G * kSwgStride;
         u32 W = 0, C = 0;
         for (u32 w = tid; w < upto; w += B) {
             const u32* rec = swg_row + (size_t)w * kSwgStride;
@@ -394,13 +418,23 @@ __device__ __forceinline__ void classify_phase(const Source& src, const Params& 
         block_sum2<B>(W, C, sm.red);
         runW += W;
         runC = C;
+        if (wg < records && !sel.emit_all) {
+            const u32* rec = swg_row + (size_t)wg * kSwgStride;
+            myC = rec[sel.bin] - rec[sel.bin + 1];
+        }
         if (wg == 0) {
-            // the next pass accumulates into the other histogram buffer: clear it now
-            u32* other = P.ghist + ((size_t)((p + 1) & 1) * P.batch + row) * kMaxBins;
+            // histogram buffer (p + 2) % 3 was read by the previous pass and is filled by the next one: clear it
+            u32* other = P.ghist + ((size_t)((p + 2) % 3) * P.batch + row) * kMaxBins;
             for (int j = tid; j < kMaxBins; j += B) other[j] = 0;
         }
     }
     if (wg == 0 && tid == 0) write_pass_record(st, p, ctx.pi, e, sel, where);
+
+    // the next pass: does it exist, and will the many-workgroup kernels run it?
+    const bool count_next = !sel.emit_all && p + 1 < P.npass;
+    const bool next_multi = !SINGLE && count_next && sel.inside > P.small;
+    const PassInfo next_pi = P.pass[p + 1 < P.npass ? p + 1 : p];
+    const int nb_next = 1 << next_pi.bits;
 
     ClassifyOut<DT> o;
     o.out_v = (char*)P.out_values + (size_t)row * (size_t)P.k * KeyOf<DT>::kBytes;
@@ -434,6 +468,9 @@ __device__ __forceinline__ void classify_phase(const Source& src, const Params& 
         }
     }
 
+    __syncthreads();  // everyone has read the suffix sums: the LDS histogram is free for the next digit
+    if (count_next)
+        for (int j = tid; j < nb_next; j += B) sm.hist[j] = 0;
     if (tid == 0) {
         sm.runW = runW;
         sm.runC = runC;
@@ -441,23 +478,54 @@ __device__ __forceinline__ void classify_phase(const Source& src, const Params& 
     __syncthreads();
     WriteState ws;
     ws.fillW = ws.fillC = 0;
+    NextCount nc;
+    nc.hist = count_next ? sm.hist : nullptr;
+    nc.pi = next_pi;
+    nc.dirmask = ctx.dirmask;
+    nc.idx_max = ctx.idx_max;
+    nc.a_s = ctx.a_s;
+    // tiles of X are dealt round-robin to the row's workgroups; a candidate segment belongs to one workgroup
     for_each_tile<SINGLE ? 1 : 2>(
-        src, wg, G, ntiles,
+        src, own_segment ? 0u : wg, own_segment ? 1u : G, ntiles,
         [&](const typename Source::Tile& cur) {
             if constexpr (SRC != SRC_RUNTIME) {
                 if (floatcmp)
-                    classify_tile<true, true, Source, DT, SRC, B>(src, cur, ctx, o, sm, lane, wave, ws);
+                    classify_tile<true, true, Source, DT, SRC, B>(src, cur, ctx, o, sm, lane, wave, ws, nc);
                 else
-                    classify_tile<true, false, Source, DT, SRC, B>(src, cur, ctx, o, sm, lane, wave, ws);
+                    classify_tile<true, false, Source, DT, SRC, B>(src, cur, ctx, o, sm, lane, wave, ws, nc);
             } else {
-                classify_tile<true, false, Source, DT, SRC, B>(src, cur, ctx, o, sm, lane, wave, ws);
+                classify_tile<true, false, Source, DT, SRC, B>(src, cur, ctx, o, sm, lane, wave, ws, nc);
             }
         },
         [&](const typename Source::Tile& cur) {
-            classify_tile<false, false, Source, DT, SRC, B>(src, cur, ctx, o, sm, lane, wave, ws);
+            classify_tile<false, false, Source, DT, SRC, B>(src, cur, ctx, o, sm, lane, wave, ws, nc);
         });
     if (ws.fillW) flush_wave_winners<DT>(o, sm.wbuf[wave], &sm.runW, ws.fillW, lane);
-    if (ws.fillC) flush_wave_candidates<DT>(o, sm.cbuf[wave], &sm.runC, ws.fillC, lane);
+    if (ws.fillC) flush_wave_candidates<DT>(o, sm.cbuf[wave], &sm.runC, ws.fillC, lane, nc);
+
+    if (count_next) {
+        // publish the next pass's histogram: LDS -> global (agent-scope atomics), then the suffix sums the
+        // next CLASSIFY needs for its offsets, and the segment of the candidate array this workgroup wrote
+        __syncthreads();
+        if (!SINGLE) {
+            u32* gnext = P.ghist + ((size_t)((p + 1) % 3) * P.batch + row) * kMaxBins;
+            for (int j = tid; j < nb_next; j += B) {
+                const u32 c = sm.hist[j];
+                if (c) atomicAdd(&gnext[j], c);
+            }
+        }
+        if (SINGLE || next_multi) suffix_sums_in_place<B>(sm.hist, nb_next, sm.wsum);
+        if (next_multi) {
+            u32* mine = P.swg + (((size_t)((p + 1) & 1) * P.batch + row) * P.G + wg) * kSwgStride;
+            for (int j = tid; j < nb_next; j += B) mine[j] = sm.hist[j];
+            if (tid == 0) {
+                mine[nb_next] = 0;
+                u32* seg = P.seg + (((size_t)(p & 1) * P.batch + row) * P.G + wg) * 2;
+                seg[0] = runC;
+                seg[1] = myC;
+            }
+        }
+    }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -487,7 +555,7 @@ __device__ __forceinline__ void init_row(const Params& P, int row, rtopk_row_tra
 template <int DT>
 __global__ void __launch_bounds__(256) k_init(Params P) {
     const int row = blockIdx.x;
-    for (int h = 0; h < 2; ++h) {
+    for (int h = 0; h < 3; ++h) {
         u32* ghist = P.ghist + ((size_t)h * P.batch + row) * kMaxBins;
         for (int j = threadIdx.x; j < kMaxBins; j += 256) ghist[j] = 0;
     }
@@ -523,21 +591,12 @@ __global__ void __launch_bounds__(kGridBlock) k_classify_keys(Params P) {
     const PassEntry e = pass_entry(P, st, 0);
     KeySource<DT, kGridBlock, key_vecs<DT>(), NT> src;
     src.init(P.keys, P.n, row);
-    classify_phase<decltype(src), DT, SRC, kGridBlock, false>(src, P, 0, row, blockIdx.x, gridDim.x, e, st, sm, 1u);
+    const u32 ntiles = src.ntiles();
+    classify_phase<decltype(src), DT, SRC, kGridBlock, false>(src, P, 0, row, blockIdx.x, gridDim.x, e, st, sm, 1u,
+                                                              HIST_IN_GLOBAL, ntiles < gridDim.x ? ntiles : gridDim.x, false);
 }
 
-template <int DT>
-__global__ void __launch_bounds__(kGridBlock) k_hist_cand(Params P, int p) {
-    __shared__ Shared<kGridBlock> sm;
-    const int row = blockIdx.y;
-    const rtopk_row_trace* st = row_state(P, row);
-    const PassEntry e = pass_entry(P, st, p);
-    if (!multi_runs_pass(P, e, p)) return;
-    CandSource<kGridBlock, kVecs> src;
-    src.init(P.cand[(p - 1) & 1] + (size_t)row * (size_t)P.n, e.cand);
-    hist_phase<decltype(src), DT, SRC_RUNTIME, kGridBlock, false>(src, P, p, row, blockIdx.x, gridDim.x, st->a_s, sm);
-}
-
+// Pass p >= 1 on the grid: workgroup w classifies the candidates workgroup w kept in pass p - 1.
 template <int DT>
 __global__ void __launch_bounds__(kGridBlock) k_classify_cand(Params P, int p) {
     __shared__ Shared<kGridBlock> sm;
@@ -545,9 +604,12 @@ __global__ void __launch_bounds__(kGridBlock) k_classify_cand(Params P, int p) {
     rtopk_row_trace* st = row_state(P, row);
     const PassEntry e = pass_entry(P, st, p);
     if (!multi_runs_pass(P, e, p)) return;
+    const u32* seg = P.seg + (((size_t)((p - 1) & 1) * P.batch + row) * P.G + blockIdx.x) * 2;
     CandSource<kGridBlock, kVecs> src;
-    src.init(P.cand[(p - 1) & 1] + (size_t)row * (size_t)P.n, e.cand);
-    classify_phase<decltype(src), DT, SRC_RUNTIME, kGridBlock, false>(src, P, p, row, blockIdx.x, gridDim.x, e, st, sm, 1u);
+    src.init(P.cand[(p - 1) & 1] + (size_t)row * (size_t)P.n, seg[0], seg[1]);
+    // its own tiles only: the segment is this workgroup's alone
+    classify_phase<decltype(src), DT, SRC_RUNTIME, kGridBlock, false>(src, P, p, row, blockIdx.x, gridDim.x, e, st, sm, 1u,
+                                                                      HIST_IN_GLOBAL, gridDim.x, true);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -555,17 +617,20 @@ __global__ void __launch_bounds__(kGridBlock) k_classify_cand(Params P, int p) {
 // ------------------------------------------------------------------------------------------------
 
 // Remaining passes of one row on its candidate arrays, by a single workgroup, starting at pass p.
+// `hist_from` says where pass p's histogram is; every later pass finds its suffix sums in LDS, left there by
+// the pass before it.
 template <int DT>
 __device__ __forceinline__ void finish_row(const Params& P, int row, rtopk_row_trace* st, Shared<kRowBlock>& sm,
-                                           int p, u32 where) {
+                                           int p, int hist_from, u32 where) {
     for (; p < P.npass; ++p) {
         __syncthreads();  // the previous pass's record and candidates are visible to the whole workgroup
         const PassEntry e = pass_entry(P, st, p);
         if (e.finished) return;
         CandSource<kRowBlock, kVecs> src;
-        src.init(P.cand[(p - 1) & 1] + (size_t)row * (size_t)P.n, e.cand);
-        hist_phase<decltype(src), DT, SRC_RUNTIME, kRowBlock, true>(src, P, p, row, 0u, 1u, st->a_s, sm);
-        classify_phase<decltype(src), DT, SRC_RUNTIME, kRowBlock, true>(src, P, p, row, 0u, 1u, e, st, sm, where);
+        src.init(P.cand[(p - 1) & 1] + (size_t)row * (size_t)P.n, 0u, e.cand);
+        classify_phase<decltype(src), DT, SRC_RUNTIME, kRowBlock, true>(src, P, p, row, 0u, 1u, e, st, sm, where,
+                                                                        hist_from, 1u, true);
+        hist_from = HIST_IN_LDS;
     }
     __syncthreads();
     // digits exhausted: extended keys are unique, so the last pass must have taken its whole bin
@@ -579,7 +644,7 @@ __global__ void __launch_bounds__(kRowBlock) k_finish(Params P) {
     rtopk_row_trace* st = row_state(P, row);
     int p = 0;
     while (p < P.npass && st->pass_rec[p].where != 0u) ++p;  // first pass the grid kernels left undone
-    finish_row<DT>(P, row, st, sm, p, 2u);
+    finish_row<DT>(P, row, st, sm, p, HIST_IN_GLOBAL, 2u);   // its histogram was published by the pass before it
 }
 
 // Whole selection of one row in one kernel (many short rows: no global atomics, no extra launches).
@@ -595,9 +660,9 @@ __global__ void __launch_bounds__(kRowBlock) k_row(Params P) {
         KeySource<DT, kRowBlock, key_vecs<DT>(), false> src;
         src.init(P.keys, P.n, row);
         hist_phase<decltype(src), DT, SRC, kRowBlock, true>(src, P, 0, row, 0u, 1u, st->a_s, sm);
-        classify_phase<decltype(src), DT, SRC, kRowBlock, true>(src, P, 0, row, 0u, 1u, e, st, sm, 3u);
+        classify_phase<decltype(src), DT, SRC, kRowBlock, true>(src, P, 0, row, 0u, 1u, e, st, sm, 3u, HIST_IN_LDS, 1u, true);
     }
-    finish_row<DT>(P, row, st, sm, 1, 3u);
+    finish_row<DT>(P, row, st, sm, 1, HIST_IN_LDS, 3u);
 }
 
 static void mark(void* const* events, int i, hipStream_t st) {
@@ -644,7 +709,6 @@ static rtopk_status launch_all(const Params& P, const Config& c, bool scaled, hi
     }
     mark(events, 3, st);
     for (int p = 1; p < c.npass; ++p) {
-        hipLaunchKernelGGL((k_hist_cand<DT>), grid, block, 0, st, P, p);
         hipLaunchKernelGGL((k_classify_cand<DT>), grid, block, 0, st, P, p);
     }
     hipLaunchKernelGGL((k_finish<DT>), dim3(batch), dim3(kRowBlock), 0, st, P);
