@@ -148,7 +148,11 @@ typedef struct {
         uint32_t out_before;   /* outputs already written when this pass started                     */
         uint32_t cand_before;  /* candidates this pass looked at                                     */
         uint32_t window;       /* source | shift << 8 | bits << 16; source 0 scaled key, 1 key,
-                                  2 index (tie break); the digit is bits [shift, shift + bits)       */
+                                  2 index (tie break); the digit is bits [shift, shift + bits).
+                                  Source 3: not a digit pass -- at most 512 candidates were left and
+                                  were ranked against each other directly (by key, then index),
+                                  which stands for all the digit passes that would have followed;
+                                  bin and k_after are 0, winners is the number of them that won      */
     } pass_rec[RTOPK_TRACE_MAX_PASSES];
 } rtopk_row_trace;
 

@@ -14,7 +14,7 @@ namespace rtopk {
 // host side
 // ------------------------------------------------------------------------------------------------
 struct Layout {
-    size_t state_off, ghist_off, seg_off, swg_off, cand0_off, cand1_off, total;
+    size_t state_off, dbg_off, ghist_off, seg_off, swg_off, cand0_off, cand1_off, total;
 };
 
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -98,12 +98,16 @@ static Layout make_layout(int64_t batch, int64_t n, const Config& c) {
     size_t off = 0;
     L.state_off = off;
     off = align_up(off + (size_t)batch * RTOPK_TRACE_STRIDE, 256);
+    L.dbg_off = off;
+    off = align_up(off + (size_t)batch * c.G * 128, 256);
+    // global histograms, per-workgroup records and segments exist only when several workgroups share a row
+    const size_t shared_rows = c.path == 2 ? (size_t)batch : 0;
     L.ghist_off = off;
-    off = align_up(off + (size_t)3 * batch * kMaxBins * 4, 256);
+    off = align_up(off + (size_t)3 * shared_rows * kMaxBins * 4, 256);
     L.seg_off = off;
-    off = align_up(off + (size_t)2 * batch * c.G * 2 * 4, 256);
+    off = align_up(off + (size_t)2 * shared_rows * c.G * 2 * 4, 256);
     L.swg_off = off;
-    off = align_up(off + (size_t)2 * batch * c.G * kSwgStride * 4, 256);
+    off = align_up(off + (size_t)2 * shared_rows * c.G * kSwgStride * 4, 256);
     L.cand0_off = off;
     off = align_up(off + (size_t)batch * (size_t)n * 8, 256);
     L.cand1_off = off;
@@ -165,6 +169,7 @@ rtopk_status rtopk_select_events(const void* keys, int64_t batch, int64_t n, int
     P.state = (rtopk_row_trace*)(ws + L.state_off);
     P.ghist = (u32*)(ws + L.ghist_off);
     P.seg = (u32*)(ws + L.seg_off);
+    P.dbg = (unsigned long long*)(ws + L.dbg_off);
     P.swg = (u32*)(ws + L.swg_off);
     P.cand[0] = (uint2*)(ws + L.cand0_off);
     P.cand[1] = (uint2*)(ws + L.cand1_off);

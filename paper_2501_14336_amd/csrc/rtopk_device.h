@@ -35,6 +35,7 @@ struct Params {
     u32* seg;                // [2][batch][G][2]    (start, count) of the candidates each workgroup wrote, per pass parity
     u32* swg;                // [2][batch][G][kSwgStride]  per-workgroup suffix sums of its local histogram, per pass parity
     uint2* cand[2];          // [batch][n]          (raw bits, index) candidates, ping-pong
+    unsigned long long* dbg; // [batch][G][16]      optional per-workgroup timestamps (diagnostic builds only)
     long long n, k;
     int batch, G;
     u32 dirmask;             // 0 for "largest"; all key bits set for "smallest" (complements the key)
@@ -430,21 +431,31 @@ __device__ __forceinline__ void for_each_tile(const Source& src, u32 wg, u32 G, 
 // workgroup-wide scans
 // ------------------------------------------------------------------------------------------------
 
-// Inclusive prefix sum of v over the workgroup's threads.  wsum: LDS, B/64 words.  Contains barriers.
+// Inclusive prefix sum of v over the 64 lanes of a wave, on the data-parallel-primitive lane network (no
+// LDS round trips): shifts by 1, 2, 4, 8 inside each row of 16 lanes, then the last lane of rows 0 and 2 is
+// added to rows 1 and 3, then lane 31 to the upper half.  Lanes without a source read 0.
+__device__ __forceinline__ u32 wave_inclusive_scan(u32 v) {
+    v += (u32)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xf, 0xf, false);  // row_shr:1
+    v += (u32)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xf, 0xf, false);  // row_shr:2
+    v += (u32)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xf, 0xf, false);  // row_shr:4
+    v += (u32)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xf, 0xf, false);  // row_shr:8
+    v += (u32)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xa, 0xf, false);  // row_bcast:15 -> rows 1, 3
+    v += (u32)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xc, 0xf, false);  // row_bcast:31 -> rows 2, 3
+    return v;
+}
+
+// Inclusive prefix sum of v over the workgroup's threads.  wsum: LDS, B/64 words.  Contains one barrier;
+// wsum must not be written again before the workgroup's next barrier.
 template <int B>
 __device__ __forceinline__ u32 block_inclusive_scan(u32 v, u32* wsum) {
     const u32 lane = lane_id();
     const u32 wave = threadIdx.x >> 6;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        u32 t = __shfl_up(v, o, 64);
-        if (lane >= (u32)o) v += t;
-    }
+    v = wave_inclusive_scan(v);
     if (lane == 63) wsum[wave] = v;
     __syncthreads();
     u32 add = 0;
-    for (u32 w = 0; w < wave; ++w) add += wsum[w];
-    __syncthreads();
+#pragma unroll
+    for (u32 w = 0; w < (u32)(B / 64); ++w) add += w < wave ? wsum[w] : 0u;
     return v + add;
 }
 
@@ -489,34 +500,29 @@ __device__ __forceinline__ void suffix_sums_in_place(u32* h, int nb, u32* wsum) 
     __syncthreads();
 }
 
-// selectBin (Section 2.3.1): given suffix sums S in LDS, the bin b with S[b+1] < k <= S[b].
-// *sel is an LDS word.  Returns b to every thread; contains barriers.
-template <int B>
-__device__ __forceinline__ u32 select_bin(const u32* S, int nb, u32 k, u32* sel) {
-    if (threadIdx.x == 0) *sel = 0;
-    __syncthreads();
-    for (int j = threadIdx.x; j < nb; j += B) {
-        u32 sj = S[j];
-        u32 sn = (j + 1 < nb) ? S[j + 1] : 0u;
-        if (sj >= k && sn < k) *sel = (u32)j;
-    }
-    __syncthreads();
-    return *sel;
-}
-
 // countBin's inner step (Section 3.1.1): add one element to the workgroup-local histogram.
 // Lanes holding the same digit as the wave's first active lane are merged into one LDS atomic
 // (register-level aggregation, the "warp" level of the paper's Table 1); everything else goes
 // straight to the LDS atomic (the "block" level).  Called by the lanes that hold a valid element.
-__device__ __forceinline__ void hist_add_plain(u32* h, u32 dg) { atomicAdd(&h[dg], 1u); }
+// A histogram may be kept as several copies, each lane adding to copy (lane mod copies): lanes of one wave
+// that hold the same digit then fall on different LDS addresses, which matters when the digits pile into a
+// few bins (a wave's adds to one word are served one after the other).  The copies lie one after the other,
+// a word more than the bin count apart, so that the same bin of different copies is in different LDS banks.
+// HistSlot is one lane's view: the start of its copy (or of the only one).
+struct HistSlot {
+    u32* h;
+    __device__ __forceinline__ u32* at(u32 dg) const { return h + dg; }
+};
 
-__device__ __forceinline__ void hist_add(u32* h, u32 dg, u32 lane) {
+__device__ __forceinline__ void hist_add_plain(const HistSlot& hs, u32 dg) { atomicAdd(hs.at(dg), 1u); }
+
+__device__ __forceinline__ void hist_add(const HistSlot& hs, u32 dg, u32 lane) {
     const u32 d0 = __builtin_amdgcn_readfirstlane(dg);
     const bool same = dg == d0;
     const u64 m = ballot64(same);
     const u32 cnt = (u32)__popcll(m);
     const bool leader = lane == (u32)__builtin_ctzll(m);  // lowest lane of the merged group
-    if (!same || leader) atomicAdd(&h[dg], same ? cnt : 1u);
+    if (!same || leader) atomicAdd(hs.at(dg), same ? cnt : 1u);
 }
 
 }  // namespace rtopk

@@ -33,8 +33,16 @@
 #include "rtopk.h"
 #include "rtopk_device.h"
 #include "rtopk_host.h"
+#include <type_traits>
 
 namespace rtopk {
+
+// Diagnostic builds (-DRTOPK_TIMING) leave wall-clock stamps of a workgroup's phases in the workspace.
+#ifdef RTOPK_TIMING
+#define RTOPK_STAMP(i) do { if (SINGLE && threadIdx.x == 0) P.dbg[(size_t)row * P.G * 16 + (i)] = wall_clock64(); } while (0)
+#else
+#define RTOPK_STAMP(i) do { } while (0)
+#endif
 
 #ifndef RTOPK_GRID_BLOCK
 #define RTOPK_GRID_BLOCK 512
@@ -53,10 +61,18 @@ struct Shared {
     u32 hist[kMaxBins];
     u32 wsum[B / 64];
     u32 red[2 * (B / 64)];
-    u32 sel;
+    u32 selv[4];                      // selectBin's result: bin, count above it, count inside it; distrust flag
+    float a_s;                        // the row's scaling constant, broadcast by the thread that drew it
     u32 runW, runC;                   // next free output / candidate position of this workgroup's range
-    uint2 wbuf[B / 64][kStageCap];    // per-wave staged winners    (raw bits, index)
-    uint2 cbuf[B / 64][kStageCap];    // per-wave staged candidates (raw bits, index)
+    union {
+        struct {
+            uint2 wbuf[B / 64][kStageCap];  // per-wave staged winners    (raw bits, index)
+            uint2 cbuf[B / 64][kStageCap];  // per-wave staged candidates (raw bits, index)
+        };
+        // the same bytes while nothing is staged: interleaved copies of the histogram a single workgroup
+        // builds of its whole row
+        u32 wide[4 * (B / 64) * kStageCap + 32];
+    };
 };
 
 // Loop state on entry to pass p (Algorithm 1's candidates / k, plus the output fill level).
@@ -66,7 +82,13 @@ struct PassEntry {
     u32 out_before;  // outputs already written
     bool finished;   // an earlier pass completed the row
     bool prev_multi; // the previous pass was run by the many-workgroup kernels
+    bool in_lds;     // the candidates are in the workgroup's LDS list (few of them), not in the candidate array
 };
+
+// Few enough candidates are ranked directly against each other (one per lane) instead of walking the
+// remaining digits; the list lives where the LDS histogram is, which no longer has a use then.
+constexpr u32 kRankCap = 512;
+constexpr int SRC_RANK = 3;  // `window` source code of the record the ranking step leaves
 
 __device__ __forceinline__ PassEntry pass_entry(const Params& P, const rtopk_row_trace* st, int p) {
     PassEntry e;
@@ -76,12 +98,14 @@ __device__ __forceinline__ PassEntry pass_entry(const Params& P, const rtopk_row
         e.out_before = 0;
         e.finished = false;
         e.prev_multi = true;
+        e.in_lds = false;
     } else {
         e.cand = st->pass_rec[p - 1].cand_after;
         e.k_rem = st->pass_rec[p - 1].k_after;
         e.out_before = st->pass_rec[p - 1].out_before + st->pass_rec[p - 1].winners;
         e.finished = e.cand == 0;
         e.prev_multi = st->pass_rec[p - 1].where == 1u;
+        e.in_lds = false;
     }
     return e;
 }
@@ -95,18 +119,83 @@ struct Selection {
     bool emit_all;  // inside == k_inside: the whole bin wins and the row is finished
 };
 
-// selectBin (Section 2.3.1) on suffix sums S held in LDS.  Contains barriers.
-template <int B>
-__device__ __forceinline__ Selection select_on_suffix_sums(const u32* S, int nb, u32 k_rem, u32* sel,
-                                                           rtopk_row_trace* st) {
+// selectBin (Section 2.3.1): the bin b with S[b+1] < k <= S[b], S[j] = number of candidates whose digit is at
+// least j, together with S[b+1] and the bin's own count.  count(j) reads bin j's count (LDS or global).
+// The suffix sums are never stored: every thread sums a few consecutive bins (from the top bin down), one
+// scan over the workgroup gives each thread the count above its bins, and the one thread whose range
+// contains the k-th candidate walks its bins.  Two barriers; count() is not called after the first, and
+// after_read() runs between them (the place to recycle the memory the counts were in).
+// A count function may also report that its bins cannot be trusted (see hist_tile_raw): count(j, &bad).
+template <int B, class Count, class AfterRead>
+__device__ __forceinline__ Selection select_from_counts(Count&& count, int nb, u32 k_rem, Shared<B>& sm,
+                                                        rtopk_row_trace* st, AfterRead&& after_read, bool* distrust) {
+    constexpr int kMaxPer = kMaxBins / B;
+    const int ipt = (nb + B - 1) / B;
+    const int r0 = threadIdx.x * ipt;  // position counted from the TOP bin
+    u32 c[kMaxPer];
+    u32 s = 0;
+    bool bad = false;
+#pragma unroll
+    for (int i = 0; i < kMaxPer; ++i) {
+        const int r = r0 + i;
+        c[i] = (i < ipt && r < nb) ? count((u32)(nb - 1 - r), &bad) : 0u;
+        s += c[i];
+    }
+    if (threadIdx.x == 0) sm.selv[0] = sm.selv[1] = sm.selv[2] = sm.selv[3] = 0;
+    const u32 incl = block_inclusive_scan<B>(s, sm.wsum);
+    after_read();
+    const u32 before = incl - s;  // candidates in bins above this thread's
+    if (before < k_rem && k_rem <= incl) {
+        u32 run = before;
+#pragma unroll
+        for (int i = 0; i < kMaxPer; ++i) {
+            if (run < k_rem && k_rem <= run + c[i]) {
+                sm.selv[0] = (u32)(nb - 1 - (r0 + i));
+                sm.selv[1] = run;
+                sm.selv[2] = c[i];
+            }
+            run += c[i];
+        }
+    }
+    if (bad) sm.selv[3] = 1u;
+    if (threadIdx.x == B - 1 && !distrust && (k_rem == 0 || k_rem > incl)) st->error |= 1u;  // never expected
+    __syncthreads();
     Selection r;
-    r.bin = select_bin<B>(S, nb, k_rem, sel);
-    r.above = (r.bin + 1 < (u32)nb) ? S[r.bin + 1] : 0u;
-    r.inside = S[r.bin] - r.above;
+    r.bin = sm.selv[0];
+    r.above = sm.selv[1];
+    r.inside = sm.selv[2];
     r.k_inside = k_rem - r.above;
     r.emit_all = r.inside == r.k_inside;
-    if (threadIdx.x == 0 && (k_rem == 0 || k_rem > S[0])) st->error |= 1u;  // inconsistent state: never expected
+    if (distrust) *distrust = sm.selv[3] != 0u;
     return r;
+}
+
+// selectBin for pass entry e, plus the housekeeping that fits between its barriers: the LDS histogram is
+// cleared for the next digit's counts and the workgroup's running write positions start at the row's
+// (a workgroup that shares the row adds its own offsets afterwards).
+template <int B, class Count>
+__device__ __forceinline__ Selection select_pass(Count&& count, int nb, const PassEntry& e, Shared<B>& sm,
+                                                 rtopk_row_trace* st, bool* distrust = nullptr) {
+    return select_from_counts<B>(
+        count, nb, e.k_rem, sm, st,
+        [&]() __attribute__((always_inline)) {
+            for (int j = threadIdx.x; j < kMaxBins; j += B) sm.hist[j] = 0;
+            if (threadIdx.x == 0) {
+                sm.runW = e.out_before;
+                sm.runC = 0;
+            }
+        },
+        distrust);
+}
+// The usual count functions: a plain array of bin counts in LDS or in global memory.
+struct PlainCounts {
+    const u32* c;
+    __device__ __forceinline__ u32 operator()(u32 j, bool*) const { return c[j]; }
+};
+
+// The row's global histogram for pass p (three buffers in rotation: read p % 3, fill (p + 1) % 3, clear the third).
+__device__ __forceinline__ u32* global_hist(const Params& P, int p, int row) {
+    return P.ghist + ((size_t)(p % 3) * P.batch + row) * kMaxBins;
 }
 
 __device__ __forceinline__ void write_pass_record(rtopk_row_trace* st, int p, const PassInfo pi, const PassEntry& e,
@@ -142,7 +231,7 @@ __device__ __forceinline__ void vector_digits(const Source& src, const typename 
 // is hot); otherwise every lane issues its own atomic (cheapest when digits are spread).
 template <bool FULL, bool MERGE, class Source, int DT, int SRC>
 __device__ __forceinline__ void hist_tile(const Source& src, const typename Source::Tile& t, const DigitCtx& c,
-                                          u32* hist, u32 lane) {
+                                          const HistSlot& hist, u32 lane) {
     constexpr int E = Source::E;
 #pragma unroll
     for (int u = 0; u < Source::kSlots / E; ++u) {
@@ -174,42 +263,175 @@ __device__ __forceinline__ u32 hot_lanes(const Source& src, const typename Sourc
     return (u32)__popcll(ballot64(dg[0] == d0));
 }
 
-template <class Source, int DT, int SRC, int B, bool SINGLE>
-__device__ __forceinline__ void hist_phase(const Source& src, const Params& P, int p, int row, u32 wg, u32 G,
-                                           float a_s, Shared<B>& sm) {
+// The first digit of a key is a one-to-one function of the top bits of the element's own bit pattern -- set
+// the sign bit of non-negatives, complement negatives (then everything, for "smallest") -- for every element
+// that is not a NaN: all NaNs share one key whatever their bits.  So a row can be counted by its raw top bits
+// (one or two instructions per element instead of the key transform) and the bins renamed afterwards, as long
+// as the raw bins that could hold a NaN (exponent field all ones, which also covers the infinities) turn out
+// empty; if they do not, the caller counts again with the exact transform.
+template <bool FULL, class Source>
+__device__ __forceinline__ void hist_tile_raw(const Source& src, const typename Source::Tile& t, const DigitCtx& c,
+                                              const HistSlot& hs) {
+    constexpr int E = Source::E;
+    auto add = [&](int s, u32 draw) __attribute__((always_inline)) {
+        if (FULL) {
+            atomicAdd(hs.at(draw), 1u);
+        } else {
+            u32 raw, idx;
+            bool valid;
+            src.get(t, s, raw, idx, valid);
+            if (valid) atomicAdd(hs.at(draw), 1u);
+        }
+    };
+#pragma unroll
+    for (int u = 0; u < Source::kSlots / E; ++u) {
+        const uint4 q = t.r[u];
+        const u32 w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (E == 4) {
+                add(u * 4 + j, w[j] >> c.pi.shift);
+            } else {  // two 16-bit elements per word; their digit windows sit in bits 16..31 of the aligned key
+                add(u * 8 + 2 * j, (w[j] & 0xffffu) >> (c.pi.shift - 16u));
+                add(u * 8 + 2 * j + 1, w[j] >> c.pi.shift);
+            }
+        }
+    }
+}
+
+// Key digit of a raw top-bits digit (see hist_tile_raw).
+__device__ __forceinline__ u32 key_digit_of_raw(u32 draw, u32 bits, bool largest) {
+    const u32 top = 1u << (bits - 1u), mask = (top << 1) - 1u;
+    const u32 dk = (draw & top) ? (~draw & mask) : (draw | top);
+    return largest ? dk : mask - dk;
+}
+
+// `Resident`: NoResident, or a callable r(f) that calls f(tile) for every tile of a row the workgroup
+// holds (or is receiving) in registers.
+struct NoResident {};
+
+// Many workgroups per row (SINGLE false): the returned Selection is meaningless (selectBin happens in CLASSIFY,
+// on the row's global histogram).  SINGLE: this workgroup owns the row, and selectBin for loop state e is done
+// here, straight on the counts.
+template <class Source, int DT, int SRC, int B, bool SINGLE, class Resident = NoResident>
+__device__ __forceinline__ Selection hist_phase(const Source& src, const Params& P, int p, int row, u32 wg, u32 G,
+                                                float a_s, const PassEntry& e, rtopk_row_trace* st, Shared<B>& sm,
+                                                const Resident& resident = Resident()) {
+    constexpr bool kResident = !std::is_same<Resident, NoResident>::value;
     const DigitCtx ctx = make_digit_ctx(P, p, a_s);
     const int nb = 1 << ctx.pi.bits;
     const u32 tid = threadIdx.x;
     const u32 lane = lane_id();
     const u32 ntiles = src.ntiles();
-    if (!SINGLE && wg >= ntiles) return;  // nothing to count; CLASSIFY ignores this workgroup's record
+    Selection none{};
+    if (!SINGLE && wg >= ntiles) return none;  // nothing to count; CLASSIFY ignores this workgroup's record
 
-    for (int j = tid; j < nb; j += B) sm.hist[j] = 0;
-    __syncthreads();
-    for_each_tile<SINGLE ? 1 : 2>(
-        src, wg, G, ntiles,
-        [&](const typename Source::Tile& cur) {
-            if (hot_lanes<Source, DT, SRC>(src, cur, ctx) >= 12u)  // wave-uniform
-                hist_tile<true, true, Source, DT, SRC>(src, cur, ctx, sm.hist, lane);
+    // One workgroup counting a whole row spreads every bin over interleaved copies (as many as fit the idle
+    // staging buffers, at most 8): real inputs put most keys in a few bins, and lanes of a wave that add to
+    // one LDS word are served one after the other.
+    HistSlot hs{sm.hist};
+    u32 copies = 1;
+    const u32 stride = (u32)nb + 1u;
+    if (SINGLE) {
+        constexpr u32 kWideLog2 = B == 1024 ? 14 : 13;
+        static_assert(sizeof(sm.wide) / 4 >= (1u << kWideLog2) + 8, "wide histogram size");
+        const u32 room = kWideLog2 - ctx.pi.bits;
+        copies = 1u << (room < 3u ? room : 3u);
+        hs.h = sm.wide + (lane & (copies - 1u)) * stride;
+    }
+    auto clear = [&]() __attribute__((always_inline)) {
+        if (SINGLE) {
+            for (u32 j = tid; j < copies * stride; j += B) sm.wide[j] = 0;
+        } else {
+            for (int j = tid; j < nb; j += B) sm.hist[j] = 0;
+        }
+        __syncthreads();
+    };
+    auto copies_of = [&](u32 j) __attribute__((always_inline)) {
+        u32 c = 0;
+        if (copies == 8u) {  // the usual case
+#pragma unroll
+            for (u32 q = 0; q < 8u; ++q) c += sm.wide[q * stride + j];
+        } else {
+            for (u32 q = 0; q < copies; ++q) c += sm.wide[q * stride + j];
+        }
+        return c;
+    };
+
+    // The single-workgroup kernels count an unscaled first digit by raw bits first (the digit window is the
+    // top of the key: shift + bits == 32).
+    constexpr bool kRawFirst = SINGLE && SRC == SRC_KEY;
+    if constexpr (kRawFirst) {
+        clear();
+        RTOPK_STAMP(5);
+        if constexpr (kResident) {
+            resident([&](const typename Source::Tile& cur) __attribute__((always_inline)) {
+                if (cur.full)
+                    hist_tile_raw<true, Source>(src, cur, ctx, hs);
+                else
+                    hist_tile_raw<false, Source>(src, cur, ctx, hs);
+            });
+        } else {
+            for_each_tile<1>(
+                src, wg, G, ntiles,
+                [&](const typename Source::Tile& cur) { hist_tile_raw<true, Source>(src, cur, ctx, hs); },
+                [&](const typename Source::Tile& cur) { hist_tile_raw<false, Source>(src, cur, ctx, hs); });
+        }
+        __syncthreads();
+        RTOPK_STAMP(6);
+        // selectBin on the raw-bit bins, visited in key order; a non-empty bin that may hold NaNs spoils it
+        const u32 top = (u32)nb >> 1, mask = (u32)nb - 1u;
+        const u32 first_special = (DT == RTOPK_F16 ? 0x7c000000u : 0x7f800000u) >> ctx.pi.shift;
+        const bool largest = P.dirmask == 0;
+        bool distrust = false;
+        const Selection sel = select_pass<B>(
+            [&](u32 keybin, bool* bad) __attribute__((always_inline)) {
+                const u32 dk = largest ? keybin : mask - keybin;
+                const u32 draw = (dk & top) ? (dk & ~top) : (~dk & mask);  // inverse of key_digit_of_raw
+                const u32 c = copies_of(draw);
+                if (c != 0 && (draw & (top - 1u)) >= first_special) *bad = true;
+                return c;
+            },
+            nb, e, sm, st, &distrust);
+        RTOPK_STAMP(7);
+        if (!distrust) return sel;
+    }
+    clear();
+    if constexpr (kResident) {
+        // (two variants only, to bound the code size: the merging one also serves partial tiles)
+        resident([&](const typename Source::Tile& cur) __attribute__((always_inline)) {
+            if (!cur.full || hot_lanes<Source, DT, SRC>(src, cur, ctx) >= 12u)
+                hist_tile<false, true, Source, DT, SRC>(src, cur, ctx, hs, lane);
             else
-                hist_tile<true, false, Source, DT, SRC>(src, cur, ctx, sm.hist, lane);
-        },
-        [&](const typename Source::Tile& cur) {
-            hist_tile<false, true, Source, DT, SRC>(src, cur, ctx, sm.hist, lane);
+                hist_tile<true, false, Source, DT, SRC>(src, cur, ctx, hs, lane);
         });
+    } else {
+        for_each_tile<SINGLE ? 1 : 2>(
+            src, wg, G, ntiles,
+            [&](const typename Source::Tile& cur) {
+                if (hot_lanes<Source, DT, SRC>(src, cur, ctx) >= 12u)  // wave-uniform
+                    hist_tile<true, true, Source, DT, SRC>(src, cur, ctx, hs, lane);
+                else
+                    hist_tile<true, false, Source, DT, SRC>(src, cur, ctx, hs, lane);
+            },
+            [&](const typename Source::Tile& cur) {
+                hist_tile<false, true, Source, DT, SRC>(src, cur, ctx, hs, lane);
+            });
+    }
     __syncthreads();
-    if (!SINGLE) {
+    if (SINGLE) {
+        return select_pass<B>([&](u32 j, bool*) __attribute__((always_inline)) { return copies_of(j); }, nb, e, sm, st);
+    } else {
         u32* ghist = P.ghist + ((size_t)(p % 3) * P.batch + row) * kMaxBins;
         for (int j = tid; j < nb; j += B) {
             u32 c = sm.hist[j];
             if (c) atomicAdd(&ghist[j], c);
         }
-    }
-    suffix_sums_in_place<B>(sm.hist, nb, sm.wsum);
-    if (!SINGLE) {
+        suffix_sums_in_place<B>(sm.hist, nb, sm.wsum);
         u32* mine = P.swg + (((size_t)(p & 1) * P.batch + row) * P.G + wg) * kSwgStride;
         for (int j = tid; j < nb; j += B) mine[j] = sm.hist[j];
         if (tid == 0) mine[nb] = 0;
+        return none;
     }
 }
 
@@ -230,6 +452,7 @@ struct ClassifyOut {
     void* out_v;         // row's output values
     long long* out_i;    // row's output indices
     uint2* cand_out;     // row's next candidate array
+    uint2* cand_lds;     // or, when the candidates are few and one workgroup owns the row, the LDS list
     u32 kk, ncap;        // capacities (writes beyond them are dropped; they never happen in a consistent run)
     // integer mode: an element wins iff (int)digit > bw (bin, or bin - 1 when the whole bin wins) and stays a
     // candidate iff digit == b and it does not win
@@ -311,7 +534,7 @@ __device__ __noinline__ void flush_wave_winners(const ClassifyOut<DT>& o, const 
 // What the candidate flush needs to count the next pass's digit (countBin of pass p + 1 happens here, on
 // full waves, rather than element by element in the sweep).
 struct NextCount {
-    u32* hist;        // LDS histogram of the next digit, or nullptr when there is no next pass
+    HistSlot hist;    // LDS histogram of the next digit (hist.h == nullptr when there is no next pass)
     PassInfo pi;
     u32 dirmask, idx_max;
     float a_s;
@@ -327,8 +550,12 @@ __device__ __noinline__ void flush_wave_candidates(const ClassifyOut<DT>& o, con
     for (u32 i = lane; i < fill; i += 64) {
         const uint2 e = buf[i];
         const u32 pos = base + i;
-        if (pos < o.ncap) o.cand_out[pos] = e;
-        if (nc.hist) hist_add(nc.hist, digit_of<DT, SRC_RUNTIME>(nc.pi, e.x, e.y, nc.dirmask, nc.idx_max, nc.a_s), lane);
+        if (o.cand_lds) {
+            if (pos < kRankCap) o.cand_lds[pos] = e;
+        } else if (pos < o.ncap) {
+            o.cand_out[pos] = e;
+        }
+        if (nc.hist.h) hist_add(nc.hist, digit_of<DT, SRC_RUNTIME>(nc.pi, e.x, e.y, nc.dirmask, nc.idx_max, nc.a_s), lane);
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
 }
@@ -339,7 +566,8 @@ struct WriteState {
 };
 
 // One tile, one sweep over its slots: classify, append survivors to the wave's buffers.
-template <bool FULL, bool FLOATCMP, class Source, int DT, int SRC, int B>
+// RARE: survivors are expected to be few (fully unrolled callers: keeps the append code off the straight path).
+template <bool FULL, bool FLOATCMP, class Source, int DT, int SRC, int B, bool RARE = false>
 __device__ __forceinline__ void classify_tile(const Source& src, const typename Source::Tile& t, const DigitCtx& c,
                                               const ClassifyOut<DT>& o, Shared<B>& sm, u32 lane, u32 wave,
                                               WriteState& ws, const NextCount& nc) {
@@ -352,7 +580,8 @@ __device__ __forceinline__ void classify_tile(const Source& src, const typename 
     for (int s = 0; s < S; ++s) {
         u64 mw, mc;
         slot_masks<FULL, FLOATCMP, Source, DT, SRC>(src, t, s, c, o, mw, mc);
-        if (mw | mc) {
+        const bool any = (mw | mc) != 0;
+        if (RARE ? __builtin_expect(any, false) : any) {
             u32 raw, idx;
             bool valid;
             src.get(t, s, raw, idx, valid);
@@ -376,33 +605,30 @@ __device__ __forceinline__ void classify_tile(const Source& src, const typename 
     }
 }
 
-// Where the histogram of the pass comes from.
+// Where the histogram of a pass is.
 enum { HIST_IN_LDS = 0, HIST_IN_GLOBAL = 1 };
 
-// SINGLE: the row is handled by this workgroup alone (wg = 0, G = 1); suffix sums of the pass's histogram are
-// in LDS (HIST_IN_LDS) or the histogram is in the row's global buffer (HIST_IN_GLOBAL, first pass of k_finish).
-// Otherwise G workgroups share the row and the histogram is always global.
-template <class Source, int DT, int SRC, int B, bool SINGLE>
-__device__ __forceinline__ void classify_phase(const Source& src, const Params& P, int p, int row, u32 wg, u32 G,
-                                               const PassEntry& e, rtopk_row_trace* st, Shared<B>& sm, u32 where,
-                                               int hist_from, u32 records, bool own_segment) {
-    const DigitCtx ctx = make_digit_ctx(P, p, st->a_s);
+// `sel` is selectBin's decision for this pass, made by select_pass (which also prepared the LDS histogram and
+// the running write positions).  SINGLE: the row is handled by this workgroup alone (wg = 0, G = 1);
+// otherwise G workgroups share the row.
+// Returns the loop state for pass p + 1 (what the pass record written here says, without the trip through memory).
+template <class Source, int DT, int SRC, int B, bool SINGLE, class Resident = NoResident>
+__device__ __forceinline__ PassEntry classify_phase(const Source& src, const Params& P, int p, int row, u32 wg, u32 G,
+                                                    const PassEntry& e, rtopk_row_trace* st, float a_s, Shared<B>& sm,
+                                                    u32 where, const Selection& sel, u32 records, bool own_segment,
+                                                    const Resident& resident = Resident()) {
+    constexpr bool kResident = !std::is_same<Resident, NoResident>::value;
+    const DigitCtx ctx = make_digit_ctx(P, p, a_s);
     const int nb = 1 << ctx.pi.bits;
     const u32 tid = threadIdx.x;
     const u32 lane = lane_id();
     const u32 wave = tid >> 6;
     const u32 ntiles = src.ntiles();
 
+#ifdef RTOPK_TIMING
+    unsigned long long t_begin = wall_clock64(), t_pro = 0, t_sweep = 0;
+#endif
     u32 runW = e.out_before, runC = 0, myC = 0;
-    if (hist_from == HIST_IN_GLOBAL) {
-        // every workgroup repeats selectBin on the row's global histogram (cheap, and it spares a
-        // grid-wide hand-off)
-        const u32* ghist = P.ghist + ((size_t)(p % 3) * P.batch + row) * kMaxBins;
-        for (int j = tid; j < nb; j += B) sm.hist[j] = ghist[j];
-        __syncthreads();
-        suffix_sums_in_place<B>(sm.hist, nb, sm.wsum);
-    }
-    const Selection sel = select_on_suffix_sums<B>(sm.hist, nb, e.k_rem, &sm.sel, st);
     if (!SINGLE) {
         // exact write offsets: sum, at the chosen bin, the stored suffix sums of the workgroups before this one
         // (`records` workgroups have a record for this pass)
@@ -430,8 +656,12 @@ __device__ __forceinline__ void classify_phase(const Source& src, const Params& 
     }
     if (wg == 0 && tid == 0) write_pass_record(st, p, ctx.pi, e, sel, where);
 
+    // few candidates left and the row is this workgroup's alone: keep them in LDS for the ranking step
+    // (which orders by key and index, so every scaled-key digit must have been used by then)
+    const bool to_rank = SINGLE && !sel.emit_all && sel.inside <= kRankCap && p + 1 < P.npass &&
+                         P.pass[p + 1].src != SRC_SCALED;
     // the next pass: does it exist, and will the many-workgroup kernels run it?
-    const bool count_next = !sel.emit_all && p + 1 < P.npass;
+    const bool count_next = !sel.emit_all && p + 1 < P.npass && !to_rank;
     const bool next_multi = !SINGLE && count_next && sel.inside > P.small;
     const PassInfo next_pi = P.pass[p + 1 < P.npass ? p + 1 : p];
     const int nb_next = 1 << next_pi.bits;
@@ -440,6 +670,7 @@ __device__ __forceinline__ void classify_phase(const Source& src, const Params& 
     o.out_v = (char*)P.out_values + (size_t)row * (size_t)P.k * KeyOf<DT>::kBytes;
     o.out_i = P.out_indices + (size_t)row * (size_t)P.k;
     o.cand_out = P.cand[p & 1] + (size_t)row * (size_t)P.n;
+    o.cand_lds = to_rank ? (uint2*)sm.hist : nullptr;
     o.kk = (u32)P.k;
     o.ncap = (u32)P.n;
     o.b = sel.bin;
@@ -468,22 +699,33 @@ __device__ __forceinline__ void classify_phase(const Source& src, const Params& 
         }
     }
 
-    __syncthreads();  // everyone has read the suffix sums: the LDS histogram is free for the next digit
-    if (count_next)
-        for (int j = tid; j < nb_next; j += B) sm.hist[j] = 0;
-    if (tid == 0) {
-        sm.runW = runW;
-        sm.runC = runC;
+    if (!SINGLE) {
+        if (tid == 0) {
+            sm.runW = runW;
+            sm.runC = runC;
+        }
+        __syncthreads();
     }
-    __syncthreads();
+#ifdef RTOPK_TIMING
+    t_pro = wall_clock64();
+    if (p == 0) RTOPK_STAMP(8);
+#endif
     WriteState ws;
     ws.fillW = ws.fillC = 0;
     NextCount nc;
-    nc.hist = count_next ? sm.hist : nullptr;
+    nc.hist = HistSlot{count_next ? sm.hist : nullptr};
     nc.pi = next_pi;
     nc.dirmask = ctx.dirmask;
     nc.idx_max = ctx.idx_max;
     nc.a_s = ctx.a_s;
+    if constexpr (kResident && SRC != SRC_RUNTIME) {
+        resident([&](const typename Source::Tile& cur) __attribute__((always_inline)) {
+            if (cur.full && floatcmp)
+                classify_tile<true, true, Source, DT, SRC, B, true>(src, cur, ctx, o, sm, lane, wave, ws, nc);
+            else
+                classify_tile<false, false, Source, DT, SRC, B, true>(src, cur, ctx, o, sm, lane, wave, ws, nc);
+        });
+    } else
     // tiles of X are dealt round-robin to the row's workgroups; a candidate segment belongs to one workgroup
     for_each_tile<SINGLE ? 1 : 2>(
         src, own_segment ? 0u : wg, own_segment ? 1u : G, ntiles,
@@ -503,6 +745,10 @@ __device__ __forceinline__ void classify_phase(const Source& src, const Params& 
     if (ws.fillW) flush_wave_winners<DT>(o, sm.wbuf[wave], &sm.runW, ws.fillW, lane);
     if (ws.fillC) flush_wave_candidates<DT>(o, sm.cbuf[wave], &sm.runC, ws.fillC, lane, nc);
 
+#ifdef RTOPK_TIMING
+    t_sweep = wall_clock64();
+    if (p == 0) RTOPK_STAMP(9);
+#endif
     if (count_next) {
         // publish the next pass's histogram: LDS -> global (agent-scope atomics), then the suffix sums the
         // next CLASSIFY needs for its offsets, and the segment of the candidate array this workgroup wrote
@@ -514,7 +760,7 @@ __device__ __forceinline__ void classify_phase(const Source& src, const Params& 
                 if (c) atomicAdd(&gnext[j], c);
             }
         }
-        if (SINGLE || next_multi) suffix_sums_in_place<B>(sm.hist, nb_next, sm.wsum);
+        if (next_multi) suffix_sums_in_place<B>(sm.hist, nb_next, sm.wsum);
         if (next_multi) {
             u32* mine = P.swg + (((size_t)((p + 1) & 1) * P.batch + row) * P.G + wg) * kSwgStride;
             for (int j = tid; j < nb_next; j += B) mine[j] = sm.hist[j];
@@ -526,6 +772,22 @@ __device__ __forceinline__ void classify_phase(const Source& src, const Params& 
             }
         }
     }
+#ifdef RTOPK_TIMING
+    if (!SINGLE && p == 0 && tid == 0) {
+        unsigned long long* d = P.dbg + ((size_t)row * P.G + wg) * 16;
+        u32 hwid;
+        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hwid));
+        d[0] = t_begin; d[1] = t_pro; d[2] = t_sweep; d[3] = wall_clock64(); d[4] = hwid;
+    }
+#endif
+    PassEntry next;
+    next.cand = sel.emit_all ? 0u : sel.inside;
+    next.k_rem = sel.emit_all ? 0u : sel.k_inside;
+    next.out_before = e.out_before + sel.above + (sel.emit_all ? sel.inside : 0u);
+    next.finished = sel.emit_all;
+    next.prev_multi = !SINGLE;
+    next.in_lds = to_rank;
+    return next;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -538,18 +800,22 @@ __device__ __forceinline__ u64 mix64(u64 z) {
     return z;
 }
 
+// Called by every thread of a workgroup of at least 128 threads; returns a_s to thread 0 only.
 template <int DT>
-__device__ __forceinline__ void init_row(const Params& P, int row, rtopk_row_trace* st) {
-    // called by one thread
+__device__ __forceinline__ float init_row(const Params& P, int row, rtopk_row_trace* st) {
+    static_assert(sizeof(rtopk_row_trace) / 4 <= 128 && offsetof(rtopk_row_trace, a_s) == 0, "trace layout");
     u32* w = (u32*)st;
-    for (int i = 0; i < (int)(sizeof(rtopk_row_trace) / 4); ++i) w[i] = 0;
+    if (threadIdx.x >= 1 && threadIdx.x < sizeof(rtopk_row_trace) / 4) w[threadIdx.x] = 0;
     float a_s = 0.0f;
-    if (DT == RTOPK_F32 && (P.flags & RTOPK_FLAG_SCALING)) {
-        const u64 j = mix64(P.seed + 0x9E3779B97F4A7C15ull * (u64)(row + 1)) % (u64)P.n;
-        const u32 bits = ((const u32*)P.keys)[(size_t)row * (size_t)P.n + j];
-        if ((bits & 0x7f800000u) != 0x7f800000u) a_s = __uint_as_float(bits);  // finite only
+    if (threadIdx.x == 0) {
+        if (DT == RTOPK_F32 && (P.flags & RTOPK_FLAG_SCALING)) {
+            const u64 j = mix64(P.seed + 0x9E3779B97F4A7C15ull * (u64)(row + 1)) % (u64)P.n;
+            const u32 bits = ((const u32*)P.keys)[(size_t)row * (size_t)P.n + j];
+            if ((bits & 0x7f800000u) != 0x7f800000u) a_s = __uint_as_float(bits);  // finite only
+        }
+        st->a_s = a_s;
     }
-    st->a_s = a_s;
+    return a_s;
 }
 
 template <int DT>
@@ -559,7 +825,7 @@ __global__ void __launch_bounds__(256) k_init(Params P) {
         u32* ghist = P.ghist + ((size_t)h * P.batch + row) * kMaxBins;
         for (int j = threadIdx.x; j < kMaxBins; j += 256) ghist[j] = 0;
     }
-    if (threadIdx.x == 0) init_row<DT>(P, row, row_state(P, row));
+    init_row<DT>(P, row, row_state(P, row));
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -577,10 +843,11 @@ template <int DT, int SRC, bool NT>
 __global__ void __launch_bounds__(kGridBlock) k_hist_keys(Params P) {
     __shared__ Shared<kGridBlock> sm;
     const int row = blockIdx.y;
-    const rtopk_row_trace* st = row_state(P, row);
+    rtopk_row_trace* st = row_state(P, row);
     KeySource<DT, kGridBlock, key_vecs<DT>(), NT> src;
     src.init(P.keys, P.n, row);
-    hist_phase<decltype(src), DT, SRC, kGridBlock, false>(src, P, 0, row, blockIdx.x, gridDim.x, st->a_s, sm);
+    hist_phase<decltype(src), DT, SRC, kGridBlock, false>(src, P, 0, row, blockIdx.x, gridDim.x, st->a_s,
+                                                          pass_entry(P, st, 0), st, sm);
 }
 
 template <int DT, int SRC, bool NT>
@@ -592,8 +859,10 @@ __global__ void __launch_bounds__(kGridBlock) k_classify_keys(Params P) {
     KeySource<DT, kGridBlock, key_vecs<DT>(), NT> src;
     src.init(P.keys, P.n, row);
     const u32 ntiles = src.ntiles();
-    classify_phase<decltype(src), DT, SRC, kGridBlock, false>(src, P, 0, row, blockIdx.x, gridDim.x, e, st, sm, 1u,
-                                                              HIST_IN_GLOBAL, ntiles < gridDim.x ? ntiles : gridDim.x, false);
+    // every workgroup repeats selectBin on the row's global histogram (cheap, and it spares a grid-wide hand-off)
+    const Selection sel = select_pass<kGridBlock>(PlainCounts{global_hist(P, 0, row)}, 1 << P.pass[0].bits, e, sm, st);
+    classify_phase<decltype(src), DT, SRC, kGridBlock, false>(src, P, 0, row, blockIdx.x, gridDim.x, e, st, st->a_s, sm, 1u,
+                                                              sel, ntiles < gridDim.x ? ntiles : gridDim.x, false);
 }
 
 // Pass p >= 1 on the grid: workgroup w classifies the candidates workgroup w kept in pass p - 1.
@@ -608,33 +877,98 @@ __global__ void __launch_bounds__(kGridBlock) k_classify_cand(Params P, int p) {
     CandSource<kGridBlock, kVecs> src;
     src.init(P.cand[(p - 1) & 1] + (size_t)row * (size_t)P.n, seg[0], seg[1]);
     // its own tiles only: the segment is this workgroup's alone
-    classify_phase<decltype(src), DT, SRC_RUNTIME, kGridBlock, false>(src, P, p, row, blockIdx.x, gridDim.x, e, st, sm, 1u,
-                                                                      HIST_IN_GLOBAL, gridDim.x, true);
+    const Selection sel = select_pass<kGridBlock>(PlainCounts{global_hist(P, p, row)}, 1 << P.pass[p].bits, e, sm, st);
+    classify_phase<decltype(src), DT, SRC_RUNTIME, kGridBlock, false>(src, P, p, row, blockIdx.x, gridDim.x, e, st, st->a_s,
+                                                                      sm, 1u, sel, gridDim.x, true);
 }
 
 // ------------------------------------------------------------------------------------------------
 // one workgroup per row
 // ------------------------------------------------------------------------------------------------
 
-// Remaining passes of one row on its candidate arrays, by a single workgroup, starting at pass p.
-// `hist_from` says where pass p's histogram is; every later pass finds its suffix sums in LDS, left there by
-// the pass before it.
+// The ranking step: C <= kRankCap candidates, one per lane, are ordered directly by their extended key
+// (ordered key, then idx_max - index: all distinct).  A candidate's rank is the number of candidates that
+// beat it; the k_rem best go to the output at the position their rank gives, so this part of the output is
+// written in rank order.  It stands for every digit pass still to come (same winners as Algorithm 1's
+// remaining iterations would find, since those order by exactly these bits), and leaves one record.
 template <int DT>
-__device__ __forceinline__ void finish_row(const Params& P, int row, rtopk_row_trace* st, Shared<kRowBlock>& sm,
-                                           int p, int hist_from, u32 where) {
-    for (; p < P.npass; ++p) {
-        __syncthreads();  // the previous pass's record and candidates are visible to the whole workgroup
-        const PassEntry e = pass_entry(P, st, p);
-        if (e.finished) return;
-        CandSource<kRowBlock, kVecs> src;
-        src.init(P.cand[(p - 1) & 1] + (size_t)row * (size_t)P.n, 0u, e.cand);
-        classify_phase<decltype(src), DT, SRC_RUNTIME, kRowBlock, true>(src, P, p, row, 0u, 1u, e, st, sm, where,
-                                                                        hist_from, 1u, true);
-        hist_from = HIST_IN_LDS;
+__device__ __forceinline__ void rank_finish(const Params& P, int row, rtopk_row_trace* st, Shared<kRowBlock>& sm, int p,
+                                            const PassEntry& e, u32 where) {
+    static_assert(kRankCap + 8 <= (u32)kRowBlock && kRankCap * 16 + 64 <= sizeof(sm.hist), "one lane per candidate");
+    const u32 tid = threadIdx.x;
+    const u32 C = e.cand;
+    uint2* list = (uint2*)sm.hist;                    // (raw bits, index)
+    u64* ext = (u64*)(sm.hist + 2 * kRankCap);        // extended keys
+    if (!e.in_lds) {
+        const uint2* cand = P.cand[(p - 1) & 1] + (size_t)row * (size_t)P.n;
+        if (tid < C) list[tid] = cand[tid];
     }
     __syncthreads();
+    uint2 mine = make_uint2(0u, 0u);
+    u64 my = 0;
+    if (tid < C) {
+        mine = list[tid];
+        my = ((u64)(KeyOf<DT>::key(mine.x) ^ P.dirmask) << 32) | (u64)(P.idx_max - mine.y);
+        ext[tid] = my;
+    } else if (tid < C + 8u) {
+        ext[tid] = 0;
+    }
+    __syncthreads();
+    if (tid < ((C + 63u) & ~63u)) {  // whole waves: the loop's LDS reads are wave-uniform broadcasts
+        u32 rank = 0;
+        for (u32 j = 0; j < C; j += 8) {  // (the list is padded with keys that beat nobody)
+            u64 q[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) q[i] = ext[j + i];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) rank += q[i] > my ? 1u : 0u;
+        }
+        if (tid < C && rank < e.k_rem) {
+            const u32 pos = e.out_before + rank;
+            if (pos < (u32)P.k) {
+                store_value<DT>((char*)P.out_values + (size_t)row * (size_t)P.k * KeyOf<DT>::kBytes, pos, mine.x);
+                P.out_indices[(size_t)row * (size_t)P.k + pos] = (long long)mine.y;
+            }
+        }
+    }
+    if (tid == 0) {
+        if (e.k_rem == 0 || e.k_rem > C) st->error |= 1u;  // inconsistent state: never expected
+        st->pass_rec[p].bin = 0;
+        st->pass_rec[p].k_after = 0;
+        st->pass_rec[p].cand_after = 0;
+        st->pass_rec[p].winners = e.k_rem;
+        st->pass_rec[p].out_before = e.out_before;
+        st->pass_rec[p].cand_before = C;
+        st->pass_rec[p].window = SRC_RANK;
+        st->pass_rec[p].where = where;
+    }
+}
+
+// Remaining passes of one row on its candidate arrays, by a single workgroup, starting at pass p with loop
+// state e.  `hist_from` says where pass p's histogram is; every later pass finds its counts in LDS, left there
+// by the pass before it.
+template <int DT>
+__device__ __forceinline__ void finish_row(const Params& P, int row, rtopk_row_trace* st, float a_s,
+                                           Shared<kRowBlock>& sm, int p, PassEntry e, int hist_from, u32 where) {
+    for (; p < P.npass; ++p) {
+        if (e.finished) return;
+        __syncthreads();  // the previous pass's candidates are visible to the whole workgroup
+        if (e.cand <= kRankCap && P.pass[p].src != SRC_SCALED) {
+            rank_finish<DT>(P, row, st, sm, p, e, where);
+            return;
+        }
+        CandSource<kRowBlock, kVecs> src;
+        src.init(P.cand[(p - 1) & 1] + (size_t)row * (size_t)P.n, 0u, e.cand);
+        const int nb = 1 << P.pass[p].bits;
+        const Selection sel = hist_from == HIST_IN_GLOBAL
+            ? select_pass<kRowBlock>(PlainCounts{global_hist(P, p, row)}, nb, e, sm, st)
+            : select_pass<kRowBlock>(PlainCounts{sm.hist}, nb, e, sm, st);
+        e = classify_phase<decltype(src), DT, SRC_RUNTIME, kRowBlock, true>(src, P, p, row, 0u, 1u, e, st, a_s, sm, where,
+                                                                            sel, 1u, true);
+        hist_from = HIST_IN_LDS;
+    }
     // digits exhausted: extended keys are unique, so the last pass must have taken its whole bin
-    if (threadIdx.x == 0 && P.npass > 0 && st->pass_rec[P.npass - 1].cand_after != 0) st->error |= 2u;
+    if (threadIdx.x == 0 && !e.finished) st->error |= 2u;
 }
 
 template <int DT>
@@ -644,7 +978,9 @@ __global__ void __launch_bounds__(kRowBlock) k_finish(Params P) {
     rtopk_row_trace* st = row_state(P, row);
     int p = 0;
     while (p < P.npass && st->pass_rec[p].where != 0u) ++p;  // first pass the grid kernels left undone
-    finish_row<DT>(P, row, st, sm, p, HIST_IN_GLOBAL, 2u);   // its histogram was published by the pass before it
+    if (p == P.npass) return;
+    const PassEntry e = pass_entry(P, st, p);
+    finish_row<DT>(P, row, st, st->a_s, sm, p, e, HIST_IN_GLOBAL, 2u);  // its histogram was published by the pass before it
 }
 
 // Whole selection of one row in one kernel (many short rows: no global atomics, no extra launches).
@@ -653,16 +989,92 @@ __global__ void __launch_bounds__(kRowBlock) k_row(Params P) {
     __shared__ Shared<kRowBlock> sm;
     const int row = blockIdx.x;
     rtopk_row_trace* st = row_state(P, row);
-    if (threadIdx.x == 0) init_row<DT>(P, row, st);
+    const float drawn = init_row<DT>(P, row, st);
+    if (threadIdx.x == 0) sm.a_s = drawn;
     __syncthreads();
-    {
-        const PassEntry e = pass_entry(P, st, 0);
-        KeySource<DT, kRowBlock, key_vecs<DT>(), false> src;
-        src.init(P.keys, P.n, row);
-        hist_phase<decltype(src), DT, SRC, kRowBlock, true>(src, P, 0, row, 0u, 1u, st->a_s, sm);
-        classify_phase<decltype(src), DT, SRC, kRowBlock, true>(src, P, 0, row, 0u, 1u, e, st, sm, 3u, HIST_IN_LDS, 1u, true);
+    const float a_s = sm.a_s;
+    const PassEntry e = pass_entry(P, st, 0);
+    KeySource<DT, kRowBlock, key_vecs<DT>(), false> src;
+    src.init(P.keys, P.n, row);
+    const Selection sel = hist_phase<decltype(src), DT, SRC, kRowBlock, true>(src, P, 0, row, 0u, 1u, a_s, e, st, sm);
+    const PassEntry e1 = classify_phase<decltype(src), DT, SRC, kRowBlock, true>(src, P, 0, row, 0u, 1u, e, st, a_s, sm, 3u,
+                                                                                 sel, 1u, true);
+    finish_row<DT>(P, row, st, a_s, sm, 1, e1, HIST_IN_LDS, 3u);
+}
+
+// The same for a row that fits one workgroup's registers (1024 lanes x 16 vectors x 16 bytes = 256 KiB):
+// X is read from HBM exactly once -- the histogram sweep consumes the tiles as they arrive and keeps them, the
+// classify sweep runs on the registers.
+constexpr int kResidentVecs = 16;
+// f(tile) for each of the first `ntiles` tiles, unrolled by recursion: every tile must stay a named set of
+// registers (a loop over the array, even one asked to unroll, may be kept as a loop and spill the row).
+template <int C, int N, class Tile, class F>
+__device__ __forceinline__ void each_resident_tile(const Tile (&t)[N], u32 ntiles, F&& f) {
+    if constexpr (C < N) {
+        if ((u32)C < ntiles) f(t[C]);
+        each_resident_tile<C + 1>(t, ntiles, f);
     }
-    finish_row<DT>(P, row, st, sm, 1, HIST_IN_LDS, 3u);
+}
+// The same while the row is still arriving: tile C + AHEAD is requested before tile C is used, so the lanes
+// that wait for memory and the lanes that count overlap.
+template <int C, int AHEAD, int N, class Source, class F>
+__device__ __forceinline__ void each_arriving_tile(const Source& src, typename Source::Tile (&t)[N], u32 ntiles, F&& f) {
+    if constexpr (C < N) {
+        if constexpr (C + AHEAD < N)
+            if ((u32)(C + AHEAD) < ntiles) src.load(C + AHEAD, threadIdx.x, t[C + AHEAD]);
+        if ((u32)C < ntiles) f(t[C]);
+        each_arriving_tile<C + 1, AHEAD>(src, t, ntiles, f);
+    }
+}
+
+template <int DT, int SRC>
+__global__ void __launch_bounds__(kRowBlock) k_row_resident(Params P) {
+    __shared__ Shared<kRowBlock> sm;
+    typedef KeySource<DT, kRowBlock, key_vecs<DT>(), false> Source;
+    constexpr int kTiles = kResidentVecs / key_vecs<DT>();
+    constexpr int kAhead = kTiles / 2;
+    typename Source::Tile t[kTiles];
+    const int row = blockIdx.x;
+    rtopk_row_trace* st = row_state(P, row);
+    Source src;
+    src.init(P.keys, P.n, row);
+    const u32 ntiles = src.ntiles();
+#ifdef RTOPK_TIMING
+    unsigned long long tt[6];
+    tt[4] = wall_clock64();
+#endif
+    const float drawn = init_row<DT>(P, row, st);
+    if (threadIdx.x == 0) sm.a_s = drawn;
+    __syncthreads();
+    const float a_s = sm.a_s;
+    const PassEntry e = pass_entry(P, st, 0);
+    auto arriving = [&](auto&& f) __attribute__((always_inline)) {
+#pragma unroll
+        for (int c = 0; c < kAhead; ++c)
+            if ((u32)c < ntiles) src.load(c, threadIdx.x, t[c]);
+        each_arriving_tile<0, kAhead>(src, t, ntiles, f);
+    };
+    auto resident = [&](auto&& f) __attribute__((always_inline)) { each_resident_tile<0>(t, ntiles, f); };
+#ifdef RTOPK_TIMING
+    tt[0] = wall_clock64();
+#endif
+    const Selection sel = hist_phase<Source, DT, SRC, kRowBlock, true>(src, P, 0, row, 0u, 1u, a_s, e, st, sm, arriving);
+#ifdef RTOPK_TIMING
+    tt[1] = wall_clock64();
+#endif
+    const PassEntry e1 = classify_phase<Source, DT, SRC, kRowBlock, true>(src, P, 0, row, 0u, 1u, e, st, a_s, sm, 3u, sel,
+                                                                          1u, true, resident);
+#ifdef RTOPK_TIMING
+    tt[2] = wall_clock64();
+#endif
+    finish_row<DT>(P, row, st, a_s, sm, 1, e1, HIST_IN_LDS, 3u);
+#ifdef RTOPK_TIMING
+    tt[3] = wall_clock64();
+    if (threadIdx.x == 0) {
+        unsigned long long* d = P.dbg + (size_t)row * P.G * 16;
+        for (int i = 0; i < 5; ++i) d[i] = tt[i];
+    }
+#endif
 }
 
 static void mark(void* const* events, int i, hipStream_t st) {
@@ -679,7 +1091,17 @@ static rtopk_status launch_all(const Params& P, const Config& c, bool scaled, hi
         mark(events, 1, st);
         mark(events, 2, st);
         mark(events, 3, st);
-        if (scaled)
+        // does every row, lead-in included, fit the registers of one workgroup?
+        const long long cap = (long long)kRowBlock * kResidentVecs * (16 / KeyOf<DT>::kBytes);
+        // (a row that does not start on a 16-byte boundary has up to E - 1 lead-in elements in its first vector)
+        constexpr int kE = 16 / KeyOf<DT>::kBytes;
+        const bool aligned = (uintptr_t)P.keys % 16 == 0 && (batch == 1 || P.n % kE == 0);
+        const bool resident = P.n + (aligned ? 0 : kE - 1) <= cap;
+        if (resident && scaled)
+            hipLaunchKernelGGL((k_row_resident<DT, kScaledSrc>), dim3(batch), dim3(kRowBlock), 0, st, P);
+        else if (resident)
+            hipLaunchKernelGGL((k_row_resident<DT, SRC_KEY>), dim3(batch), dim3(kRowBlock), 0, st, P);
+        else if (scaled)
             hipLaunchKernelGGL((k_row<DT, kScaledSrc>), dim3(batch), dim3(kRowBlock), 0, st, P);
         else
             hipLaunchKernelGGL((k_row<DT, SRC_KEY>), dim3(batch), dim3(kRowBlock), 0, st, P);
