@@ -134,6 +134,45 @@ def test_batch_with_misaligned_rows(path):
             _run_and_check("batch misaligned", bits, dtype, k, False, tuning=dict(path=path, wgs_per_row=3))
 
 
+@pytest.mark.parametrize("dtype", [F32, BF16, F16])
+def test_rows_at_and_around_the_register_capacity(dtype):
+    # one workgroup keeps a row of up to 256 KiB in registers; one element more takes the streaming kernel.
+    # Odd lengths also give rows 1 and 2 a lead-in; k = 700 leaves more candidates than the ranking step takes.
+    cap = 65536 if dtype == F32 else 131072
+    for n in (cap - 1, cap, cap + 1):
+        x = W.normal(3 * n, 21 + n % 7, sigma=3.0)
+        x[5] = np.inf                      # the raw-bit histogram must notice it and count again exactly
+        if dtype == F32:
+            bits = x.view(np.uint32)
+        elif dtype == BF16:
+            bits = W.to_bf16_bits(x)
+        else:
+            bits = x.astype(np.float16).view(np.uint16)
+        bits = bits.reshape(3, n)
+        for k in (1, 50, 700):
+            for largest in (True, False):
+                _run_and_check("register capacity", bits, dtype, k, largest, tuning=dict(path=1))
+
+
+def test_ranking_step_breaks_ties_by_index_and_leaves_a_record():
+    # every key equal: the first digit keeps all n candidates; up to 512 of them are ranked directly (by index,
+    # keys being equal), more than that go through further digit passes first
+    for n, k in ((300, 100), (512, 1), (512, 512), (513, 100), (5000, 4990)):
+        bits = np.full(n, np.float32(2.5)).view(np.uint32)
+        for path in (1, 2):
+            tr = _run_and_check("all equal", bits, F32, k, True, tuning=dict(path=path))[0]
+            last = tr.passes[-1]
+            assert last.out_before + last.winners == k
+            if n <= 512 and k < n:
+                assert [r.source for r in tr.passes] == [1, 3] and last.cand_before == n and last.winners == k
+    # ties inside the ranked set with distinct keys around them
+    x = W.duplicates(400, seed=31)
+    for k in (1, 37, 399):
+        for largest in (True, False):
+            _run_and_check("dup ranked", x.view(np.uint32), F32, k, largest, tuning=dict(path=1))
+            _run_and_check("dup ranked bf16", W.to_bf16_bits(x), BF16, k, largest, tuning=dict(path=2, small_threshold=1))
+
+
 def test_batch_many_rows_grid_path():
     bits = W.normal(64 * 20000, 15).view(np.uint32).reshape(64, 20000)
     _run_and_check("batch 64 grid", bits, F32, 333, True, tuning=dict(path=2, small_threshold=16))
