@@ -28,7 +28,7 @@ static rtopk_status make_config(int64_t batch, int64_t n, int64_t k, rtopk_dtype
     if (flags & ~(uint32_t)RTOPK_FLAG_SCALING) return RTOPK_ERR_INVALID_ARG;
     int d = dt == RTOPK_F32 ? 12 : 11;
     int path = 0, G = 0;
-    u32 small = 32768;
+    u32 small = 65536;
     if (tn) {
         if (tn->digit_bits) {
             if (tn->digit_bits < 8 || tn->digit_bits > 12) return RTOPK_ERR_INVALID_ARG;
@@ -90,6 +90,19 @@ static rtopk_status make_config(int64_t batch, int64_t n, int64_t k, rtopk_dtype
     }
     if (np > kMaxPasses) return RTOPK_ERR_INVALID_ARG;
     c->npass = np;
+    // How far can a row keep more than `small` candidates?  Key digits may keep all n (equal keys); after an
+    // index digit at most 2^shift candidates share the bin, the indices being distinct.  Later passes are
+    // certain to fit the single-workgroup finish and get no grid launch.
+    c->multi_last = np - 1;
+    for (int p = 0; p < np; ++p) {
+        const bool idx = c->pass[p].src == SRC_IDX;
+        const uint64_t bound = idx && c->pass[p].shift < 63 && ((uint64_t)1 << c->pass[p].shift) < (uint64_t)n
+                                   ? (uint64_t)1 << c->pass[p].shift : (uint64_t)n;
+        if (bound <= small) {
+            c->multi_last = p;
+            break;
+        }
+    }
     return RTOPK_OK;
 }
 
@@ -119,6 +132,12 @@ static Layout make_layout(int64_t batch, int64_t n, const Config& c) {
 }  // namespace rtopk
 
 using namespace rtopk;
+
+// How much of a streamed row (its tail) the first sweep reads with cache-allocating loads, for the second sweep
+// to find in the caches (MI355X: 256 MB last-level cache + 32 MB of L2).  Measured on n = 2^28 fp32: the whole call takes
+// 462 us with nothing kept, 449 with 256 MB, 444-445 with 288-320 MB, 451 with 352 MB and more (the first sweep
+// slows down by more than the second gains).
+static const size_t kKeepBytes = (size_t)288 << 20;
 
 extern "C" {
 
@@ -183,7 +202,18 @@ rtopk_status rtopk_select_events(const void* keys, int64_t batch, int64_t n, int
     P.npass = c.npass;
     P.flags = flags;
     // two sweeps over more data than the 256 MB last-level cache holds: stream it past the caches
-    if ((size_t)batch * (size_t)n * (size_t)eb > ((size_t)384 << 20)) P.flags |= kInternalStream;
+    P.keep_from_tile = 0xffffffffu;
+    if ((size_t)batch * (size_t)n * (size_t)eb > ((size_t)384 << 20)) {
+        P.flags |= kInternalStream;
+        // a single long row: leave its last kKeepBytes in the last-level cache for the second sweep
+        const size_t tile_bytes = (size_t)kHostGridBlock * kHostElemsPerLane * eb;
+        const size_t row_tiles = ((size_t)n * eb + tile_bytes - 1) / tile_bytes;
+        const size_t keep_tiles = kKeepBytes / tile_bytes;
+        // (not when the second sweep writes a lot: with k = 2^24 and 2^27 of 2^28 the kept tail made the call
+        // 3 % and 7 % slower instead of 4 % faster)
+        const bool small_output = (size_t)k * (size_t)(eb + 8) <= ((size_t)32 << 20);
+        if (batch == 1 && small_output && row_tiles > keep_tiles) P.keep_from_tile = (u32)(row_tiles - keep_tiles);
+    }
     P.seed = seed;
     for (int i = 0; i < c.npass; ++i) P.pass[i] = c.pass[i];
 

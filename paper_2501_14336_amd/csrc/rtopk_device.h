@@ -43,6 +43,7 @@ struct Params {
     u32 small;               // candidate count at or below which one workgroup finishes the row
     int npass;
     u32 flags;               // RTOPK_FLAG_* | kInternalStream
+    u32 keep_from_tile;      // streamed inputs: the first sweep reads tiles from this one on with ordinary loads
     u64 seed;
     PassInfo pass[kMaxPasses];
 };
@@ -179,6 +180,7 @@ struct KeySource {
     static constexpr int E = 16 / kElemBytes;  // elements per vector
     static constexpr int kSlots = V * E;       // elements per lane per tile
     static constexpr int kTileVecs = B * V;
+    static constexpr bool kStreams = NT;
     typedef TileRegs<V> Tile;
 
     const uint4* abase;
@@ -207,6 +209,15 @@ struct KeySource {
         t.full = true;
 #pragma unroll
         for (int u = 0; u < V; ++u) t.r[u] = load16<NT>(abase + (v0 + (u64)u * B + tid));
+    }
+    // The same row read with ordinary (cache-allocating) loads.
+    __device__ __forceinline__ KeySource<DT, B, V, false> plain() const {
+        KeySource<DT, B, V, false> p;
+        p.abase = abase;
+        p.lead = lead;
+        p.n = n;
+        p.nvec = nvec;
+        return p;
     }
     __device__ __forceinline__ void load(u32 tile, u32 tid, Tile& t) const {
         u64 v0 = (u64)tile * kTileVecs;
@@ -359,65 +370,74 @@ struct CandSource {
 // are in flight while one is processed, every load in the steady state is unconditional and no register
 // set is ever copied, so the compiler can wait for exactly the oldest set instead of draining the queue.
 // The at most two partial tiles are handled afterwards, unpipelined, by fedge(tile).
+// Only tiles in [lo, hi) are visited, and the partial tiles only if `edges` (for callers that split a row
+// between two sources).
 template <int DEPTH, class Source, class FFull, class FEdge>
-__device__ __forceinline__ void for_each_tile(const Source& src, u32 wg, u32 G, u32 ntiles, FFull&& f, FEdge&& fedge) {
+__device__ __forceinline__ void for_each_tile(const Source& src, u32 wg, u32 G, u32 ntiles, FFull&& f, FEdge&& fedge,
+                                              u32 lo = 0u, u32 hi = 0xffffffffu, bool edges = true) {
     const u32 tid = threadIdx.x;
     u32 f0, f1;  // tiles [f0, f1) are full
     src.full_range(f0, f1);
+    const u32 e0 = f0, e1 = f1;  // the partial tiles are those outside [e0, e1)
+    if (f0 < lo) f0 = lo;
+    if (f1 > hi) f1 = hi;
+    if (f1 < f0) f1 = f0;
     // my first full tile and how many I own
     u32 first = wg;
     if (first < f0) first += ((f0 - first + G - 1) / G) * G;
     const u32 m = first < f1 ? (f1 - first + G - 1) / G : 0u;
+    auto tile_at = [&](u32 i) __attribute__((always_inline)) { return first + i * G; };
     if (m != 0) {
         if constexpr (DEPTH == 2) {
             typename Source::Tile a, b, c;
-            src.load_full(first, tid, a);
-            if (m > 1) src.load_full(first + G, tid, b);
+            src.load_full(tile_at(0), tid, a);
+            if (m > 1) src.load_full(tile_at(1), tid, b);
             u32 i = 0;
             // steady state: all three loads of a round exist, so every load is unconditional
             for (; i + 4 < m; i += 3) {
-                src.load_full(first + (i + 2) * G, tid, c);
+                src.load_full(tile_at(i + 2), tid, c);
                 f(a);
-                src.load_full(first + (i + 3) * G, tid, a);
+                src.load_full(tile_at(i + 3), tid, a);
                 f(b);
-                src.load_full(first + (i + 4) * G, tid, b);
+                src.load_full(tile_at(i + 4), tid, b);
                 f(c);
             }
             // at most four tiles left; a (and b, if it exists) are loaded
             f(a);
             if (i + 1 < m) f(b);
             for (u32 j = i + 2; j < m; ++j) {
-                src.load_full(first + j * G, tid, a);
+                src.load_full(tile_at(j), tid, a);
                 f(a);
             }
         } else if constexpr (DEPTH == 1) {
             typename Source::Tile a, b;
-            src.load_full(first, tid, a);
+            src.load_full(tile_at(0), tid, a);
             u32 i = 0;
             for (; i + 2 < m; i += 2) {
-                src.load_full(first + (i + 1) * G, tid, b);
+                src.load_full(tile_at(i + 1), tid, b);
                 f(a);
-                src.load_full(first + (i + 2) * G, tid, a);
+                src.load_full(tile_at(i + 2), tid, a);
                 f(b);
             }
             f(a);
             if (i + 1 < m) {
-                src.load_full(first + (i + 1) * G, tid, b);
+                src.load_full(tile_at(i + 1), tid, b);
                 f(b);
             }
         } else {
             for (u32 i = 0; i < m; ++i) {
                 typename Source::Tile a;
-                src.load_full(first + i * G, tid, a);
+                src.load_full(tile_at(i), tid, a);
                 f(a);
             }
         }
     }
-    // partial tiles: those of mine outside [f0, f1)
+    // partial tiles: those of mine outside [e0, e1)
+    if (!edges) return;
     for (u32 t = wg; t < ntiles; t += G) {
-        if (t >= f0 && t < f1) {
+        if (t >= e0 && t < e1) {
             // skip the full range in one step
-            const u32 skip = (f1 - t + G - 1) / G;
+            const u32 skip = (e1 - t + G - 1) / G;
             t += (skip - 1) * G;
             continue;
         }

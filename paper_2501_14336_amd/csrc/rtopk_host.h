@@ -11,6 +11,7 @@ struct Config {
     int d, path, G;
     u32 small;
     int npass;
+    int multi_last;  // last digit pass that may still hold more than `small` candidates (grid kernels run up to it)
     u32 idx_max, dirmask;
     PassInfo pass[kMaxPasses];
 };

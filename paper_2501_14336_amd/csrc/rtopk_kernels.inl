@@ -406,17 +406,24 @@ __device__ __forceinline__ Selection hist_phase(const Source& src, const Params&
                 hist_tile<true, false, Source, DT, SRC>(src, cur, ctx, hs, lane);
         });
     } else {
-        for_each_tile<SINGLE ? 1 : 2>(
-            src, wg, G, ntiles,
-            [&](const typename Source::Tile& cur) {
-                if (hot_lanes<Source, DT, SRC>(src, cur, ctx) >= 12u)  // wave-uniform
-                    hist_tile<true, true, Source, DT, SRC>(src, cur, ctx, hs, lane);
-                else
-                    hist_tile<true, false, Source, DT, SRC>(src, cur, ctx, hs, lane);
-            },
-            [&](const typename Source::Tile& cur) {
-                hist_tile<false, true, Source, DT, SRC>(src, cur, ctx, hs, lane);
-            });
+        auto full = [&](const typename Source::Tile& cur) {
+            if (hot_lanes<Source, DT, SRC>(src, cur, ctx) >= 12u)  // wave-uniform
+                hist_tile<true, true, Source, DT, SRC>(src, cur, ctx, hs, lane);
+            else
+                hist_tile<true, false, Source, DT, SRC>(src, cur, ctx, hs, lane);
+        };
+        auto edge = [&](const typename Source::Tile& cur) {
+            hist_tile<false, true, Source, DT, SRC>(src, cur, ctx, hs, lane);
+        };
+        if constexpr (!SINGLE && Source::kStreams) {
+            // A streamed row: everything but its tail is read with non-temporal loads; the tail is read with
+            // ordinary loads and so stays in the last-level cache, where the CLASSIFY sweep finds it (its own
+            // loads are all non-temporal and displace nothing on the way there).
+            for_each_tile<2>(src, wg, G, ntiles, full, edge, 0u, P.keep_from_tile, true);
+            for_each_tile<2>(src.plain(), wg, G, ntiles, full, edge, P.keep_from_tile, 0xffffffffu, false);
+        } else {
+            for_each_tile<SINGLE ? 1 : 2>(src, wg, G, ntiles, full, edge);
+        }
     }
     __syncthreads();
     if (SINGLE) {
@@ -1130,7 +1137,7 @@ static rtopk_status launch_all(const Params& P, const Config& c, bool scaled, hi
         hipLaunchKernelGGL((k_classify_keys<DT, SRC_KEY, false>), grid, block, 0, st, P);
     }
     mark(events, 3, st);
-    for (int p = 1; p < c.npass; ++p) {
+    for (int p = 1; p <= c.multi_last && p < c.npass; ++p) {
         hipLaunchKernelGGL((k_classify_cand<DT>), grid, block, 0, st, P, p);
     }
     hipLaunchKernelGGL((k_finish<DT>), dim3(batch), dim3(kRowBlock), 0, st, P);
