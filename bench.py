@@ -172,10 +172,10 @@ def main() -> int:
                              "algorithmic_frac_of_hbm_peak": bb / tb / 1e9 / HBM_PEAK_GBS}
         del xb, wsb
 
-    # ---- CPU baseline: the oracle as it stands, on a bounded sample of the same workload
+    # ---- CPU baseline: the oracle as it stands, on a bounded sample of the same workload (about 10-15 s)
     if not args.no_cpu_baseline:
         import oracle
-        ns = min(n, 1 << 24)
+        ns = min(n, 1 << 26)
         ks = max(1, ns * k // n)
         sample = x_host[:ns]
         c0 = time.perf_counter()

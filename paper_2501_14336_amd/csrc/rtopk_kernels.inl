@@ -3,19 +3,23 @@
 // The first digit pass (paper Section 2.3.1) is two sweeps over the input; every later pass is one sweep
 // over the candidates, because CLASSIFY also counts the NEXT digit of what it keeps:
 //
-//   HIST      countBin + selectBin.  Every workgroup builds a local histogram of the pass's digit in LDS
-//             (hierarchical atomics, Section 3.1.1), adds it to the row's global histogram, and stores the
-//             suffix sums of its local histogram.  The last workgroup of the row to finish picks the bin b
-//             that holds the k-th key and turns the stored suffix sums into exact write offsets for every
-//             workgroup, so the second sweep needs no global atomics and its output order is fixed.
-//   CLASSIFY  selectCandidate fused with the filter.  digit > b: the element is certainly in the top k and
-//             goes straight to the output (value bits + int64 index).  digit == b: it stays a candidate and
-//             is appended, with its index, to the next candidate array.  digit < b: dropped.
+//   HIST      countBin.  Every workgroup builds a local histogram of the pass's digit in LDS (hierarchical
+//             atomics, Section 3.1.1), adds it to the row's global histogram, and stores the suffix sums of
+//             its local histogram.
+//   CLASSIFY  selectBin, then selectCandidate fused with the filter.  Every workgroup picks the bin b that
+//             holds the k-th key from the row's histogram and turns the stored suffix sums of the workgroups
+//             before it into its exact write offsets, so the sweep needs no global atomics.  digit > b: the
+//             element is certainly in the top k and goes straight to the output (value bits + int64 index).
+//             digit == b: it stays a candidate and is appended, with its index, to the next candidate array.
+//             digit < b: dropped.
 //
-//   While it appends a candidate, CLASSIFY adds that candidate's next digit to a fresh LDS histogram; at its
-//   end it publishes the histogram (global atomics) and its suffix sums exactly as HIST does.  The next pass's
+//   While it writes candidates out, CLASSIFY adds their next digit to a fresh LDS histogram; at its end it
+//   publishes the histogram (global atomics) and its suffix sums exactly as HIST does.  The next pass's
 //   workgroup w then reads the segment of the candidate array that workgroup w wrote, so its per-workgroup
 //   counts are already known and no separate histogram sweep over the candidates is needed.
+//
+//   A row that one workgroup handles alone keeps all of this in LDS and registers (k_row, k_row_resident,
+//   k_finish); once at most 512 candidates are left they are ranked against each other directly.
 //
 // Passes walk the digits of the key from the most significant one down and then the digits of
 // (idx_max - index), which makes every element's extended key unique: the loop ends when the chosen
