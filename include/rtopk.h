@@ -61,7 +61,9 @@ enum {
  */
 typedef struct {
     int32_t digit_bits;      /* radix digit width d, 8..12 (default 12 for fp32, 11 for 16-bit keys)           */
-    int32_t path;            /* 0 auto, 1 one workgroup per row (fused kernel), 2 many workgroups per row      */
+    int32_t path;            /* 0 auto, 1 one workgroup per row (fused kernel), 2 many workgroups per row,
+                                3 like 1, with the one-sweep kernel for small k first (auto picks it for
+                                large batches of rows with k <= 256)                                            */
     int32_t wgs_per_row;     /* workgroups cooperating on one row in path 2 (default: fill 256 CUs)            */
     int32_t small_threshold; /* candidate count at or below which one workgroup finishes a row by itself       */
 } rtopk_tuning;
@@ -137,10 +139,15 @@ rtopk_status rtopk_select_events(const void* keys, int64_t batch, int64_t n, int
 typedef struct {
     float a_s;                 /* the element subtracted under RTOPK_FLAG_SCALING (0 if unused)      */
     uint32_t error;            /* 0, or a bit set if the device saw an impossible state              */
-    uint32_t reserved[14];
+    uint32_t redo;             /* 1: the one-sweep row kernel left this row to the two-sweep kernel
+                                  (which clears the whole record when it takes the row over)         */
+    uint32_t redo_why;         /* diagnostic, with redo: 1 inf/NaN in the first part, 2 first part
+                                  shorter than k, 3 bin edge not a number, 5 list full, 6 too many
+                                  candidates in the chosen bin, 7 list expected to overflow           */
+    uint32_t reserved[12];
     struct {
         uint32_t where;        /* 0 pass not run; 1 many workgroups; 2 single-workgroup finish;
-                                  3 fused one-workgroup-per-row kernel                               */
+                                  3 fused one-workgroup-per-row kernel; 4 one-sweep row kernel       */
         uint32_t bin;          /* chosen bin of this digit                                           */
         uint32_t k_after;      /* rank of the k-th key inside the bin (0 if the whole bin was taken) */
         uint32_t cand_after;   /* candidates passed on to the next digit (0: the row is finished)    */

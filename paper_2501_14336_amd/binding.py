@@ -58,7 +58,7 @@ class _PassRec(ctypes.Structure):
 
 
 class RtopkRowTrace(ctypes.Structure):
-    _fields_ = [("a_s", ctypes.c_float), ("error", ctypes.c_uint32), ("reserved", ctypes.c_uint32 * 14),
+    _fields_ = [("a_s", ctypes.c_float), ("error", ctypes.c_uint32), ("redo", ctypes.c_uint32), ("redo_why", ctypes.c_uint32), ("reserved", ctypes.c_uint32 * 12),
                 ("pass_rec", _PassRec * RTOPK_TRACE_MAX_PASSES)]
 
     @property

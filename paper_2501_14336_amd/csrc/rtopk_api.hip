@@ -34,7 +34,7 @@ static rtopk_status make_config(int64_t batch, int64_t n, int64_t k, rtopk_dtype
             if (tn->digit_bits < 8 || tn->digit_bits > 12) return RTOPK_ERR_INVALID_ARG;
             d = tn->digit_bits;
         }
-        if (tn->path < 0 || tn->path > 2 || tn->wgs_per_row < 0 || tn->small_threshold < 0) return RTOPK_ERR_INVALID_ARG;
+        if (tn->path < 0 || tn->path > 3 || tn->wgs_per_row < 0 || tn->small_threshold < 0) return RTOPK_ERR_INVALID_ARG;
         path = tn->path;
         G = tn->wgs_per_row;
         if (tn->small_threshold) small = (u32)tn->small_threshold;
@@ -44,6 +44,13 @@ static rtopk_status make_config(int64_t batch, int64_t n, int64_t k, rtopk_dtype
         path = (n <= (1 << 18) || (batch >= 256 && n <= (1 << 20))) ? 1 : 2;
         if (batch > 65535) path = 1;
     }
+    // The one-sweep kernel sets aside a few hundred elements of a row (its bound comes from the row's first
+    // eighth, more for larger k) and holds 2048; measured against the two-sweep kernels it wins from a few rows
+    // of 16K keys up, and on single long rows, as long as k is small.  Rows it cannot finish go to the two-sweep
+    // kernel, so the choice never changes the result.
+    bool one_sweep = path == 3;
+    if (path == 3) path = 1;
+    else if (path == 1 && (!tn || tn->path == 0) && k <= 256 && n >= 16384 && (batch >= 16 || n >= 131072)) one_sweep = true;
     if (path == 2 && batch > 65535) return RTOPK_ERR_INVALID_ARG;  // rows are the grid's y dimension
     const int eb = elem_bytes(dt);
     const int64_t tile_elems = (int64_t)kHostGridBlock * kHostElemsPerLane;  // 16 elements per lane for every type
@@ -62,6 +69,7 @@ static rtopk_status make_config(int64_t batch, int64_t n, int64_t k, rtopk_dtype
     }
     c->d = d;
     c->path = path;
+    c->one_sweep = one_sweep;
     c->G = G;
     c->small = small;
     c->dirmask = largest ? 0u : (dt == RTOPK_F32 ? 0xffffffffu : 0xffff0000u);

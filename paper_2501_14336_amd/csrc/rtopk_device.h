@@ -370,11 +370,10 @@ struct CandSource {
 // are in flight while one is processed, every load in the steady state is unconditional and no register
 // set is ever copied, so the compiler can wait for exactly the oldest set instead of draining the queue.
 // The at most two partial tiles are handled afterwards, unpipelined, by fedge(tile).
-// Only tiles in [lo, hi) are visited, and the partial tiles only if `edges` (for callers that split a row
-// between two sources).
+// Only tiles in [lo, hi) are visited (for callers that split a row into ranges).
 template <int DEPTH, class Source, class FFull, class FEdge>
 __device__ __forceinline__ void for_each_tile(const Source& src, u32 wg, u32 G, u32 ntiles, FFull&& f, FEdge&& fedge,
-                                              u32 lo = 0u, u32 hi = 0xffffffffu, bool edges = true) {
+                                              u32 lo = 0u, u32 hi = 0xffffffffu) {
     const u32 tid = threadIdx.x;
     u32 f0, f1;  // tiles [f0, f1) are full
     src.full_range(f0, f1);
@@ -433,7 +432,6 @@ __device__ __forceinline__ void for_each_tile(const Source& src, u32 wg, u32 G, 
         }
     }
     // partial tiles: those of mine outside [e0, e1)
-    if (!edges) return;
     for (u32 t = wg; t < ntiles; t += G) {
         if (t >= e0 && t < e1) {
             // skip the full range in one step
@@ -441,6 +439,7 @@ __device__ __forceinline__ void for_each_tile(const Source& src, u32 wg, u32 G, 
             t += (skip - 1) * G;
             continue;
         }
+        if (t < lo || t >= hi) continue;
         typename Source::Tile e;
         src.load(t, tid, e);
         fedge(e);

@@ -11,6 +11,7 @@ struct Config {
     int d, path, G;
     u32 small;
     int npass;
+    bool one_sweep;  // path 1: try the one-sweep kernel (small k) first
     int multi_last;  // last digit pass that may still hold more than `small` candidates (grid kernels run up to it)
     u32 idx_max, dirmask;
     PassInfo pass[kMaxPasses];

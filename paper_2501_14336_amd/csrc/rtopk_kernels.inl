@@ -130,8 +130,8 @@ struct Selection {
 // contains the k-th candidate walks its bins.  Two barriers; count() is not called after the first, and
 // after_read() runs between them (the place to recycle the memory the counts were in).
 // A count function may also report that its bins cannot be trusted (see hist_tile_raw): count(j, &bad).
-template <int B, class Count, class AfterRead>
-__device__ __forceinline__ Selection select_from_counts(Count&& count, int nb, u32 k_rem, Shared<B>& sm,
+template <int B, class Count, class AfterRead, class SM>
+__device__ __forceinline__ Selection select_from_counts(Count&& count, int nb, u32 k_rem, SM& sm,
                                                         rtopk_row_trace* st, AfterRead&& after_read, bool* distrust) {
     constexpr int kMaxPer = kMaxBins / B;
     const int ipt = (nb + B - 1) / B;
@@ -423,8 +423,8 @@ __device__ __forceinline__ Selection hist_phase(const Source& src, const Params&
             // A streamed row: everything but its tail is read with non-temporal loads; the tail is read with
             // ordinary loads and so stays in the last-level cache, where the CLASSIFY sweep finds it (its own
             // loads are all non-temporal and displace nothing on the way there).
-            for_each_tile<2>(src, wg, G, ntiles, full, edge, 0u, P.keep_from_tile, true);
-            for_each_tile<2>(src.plain(), wg, G, ntiles, full, edge, P.keep_from_tile, 0xffffffffu, false);
+            for_each_tile<2>(src, wg, G, ntiles, full, edge, 0u, P.keep_from_tile);
+            for_each_tile<2>(src.plain(), wg, G, ntiles, full, edge, P.keep_from_tile, 0xffffffffu);
         } else {
             for_each_tile<SINGLE ? 1 : 2>(src, wg, G, ntiles, full, edge);
         }
@@ -995,11 +995,13 @@ __global__ void __launch_bounds__(kRowBlock) k_finish(Params P) {
 }
 
 // Whole selection of one row in one kernel (many short rows: no global atomics, no extra launches).
+// only_redo: handle just the rows the one-sweep kernel marked.
 template <int DT, int SRC>
-__global__ void __launch_bounds__(kRowBlock) k_row(Params P) {
+__global__ void __launch_bounds__(kRowBlock) k_row(Params P, bool only_redo) {
     __shared__ Shared<kRowBlock> sm;
     const int row = blockIdx.x;
     rtopk_row_trace* st = row_state(P, row);
+    if (only_redo && st->redo != 1u) return;
     const float drawn = init_row<DT>(P, row, st);
     if (threadIdx.x == 0) sm.a_s = drawn;
     __syncthreads();
@@ -1039,11 +1041,16 @@ __device__ __forceinline__ void each_arriving_tile(const Source& src, typename S
 }
 
 template <int DT, int SRC>
-__global__ void __launch_bounds__(kRowBlock) k_row_resident(Params P) {
+__global__ void __launch_bounds__(kRowBlock) k_row_resident(Params P, bool only_redo) {
     __shared__ Shared<kRowBlock> sm;
     typedef KeySource<DT, kRowBlock, key_vecs<DT>(), false> Source;
     constexpr int kTiles = kResidentVecs / key_vecs<DT>();
+    if (only_redo && row_state(P, blockIdx.x)->redo != 1u) return;
+#ifdef RTOPK_X_AHEAD
+    constexpr int kAhead = RTOPK_X_AHEAD;
+#else
     constexpr int kAhead = kTiles / 2;
+#endif
     typename Source::Tile t[kTiles];
     const int row = blockIdx.x;
     rtopk_row_trace* st = row_state(P, row);
@@ -1088,6 +1095,326 @@ __global__ void __launch_bounds__(kRowBlock) k_row_resident(Params P) {
 #endif
 }
 
+// ------------------------------------------------------------------------------------------------
+// one workgroup per row, ONE sweep (small k)
+//
+// selectBin on any part of a row bounds the whole row's answer from below: the k-th best key of a subset
+// is never better than the k-th best of the row, so the bin b0 it falls in satisfies b0 <= b.  And selectBin
+// only ever needs the counts of the bins from b upwards.  So the kernel counts the first part of the row
+// (countBin as usual), takes b0 from it, and then sweeps the whole row once doing nothing but comparing each
+// element with the lower edge of bin b0: the few that are not below it are noted and then set aside in LDS,
+// with their index.  Those are all the elements of bins >= b0, so their histogram is the top of the row's histogram,
+// exactly: selectBin, selectCandidate and the filter run on the list.  There is no second sweep, the bulk of
+// the row is never counted, and the row is not kept anywhere, so the kernel needs few registers and little
+// LDS and three workgroups share a compute unit: one row's trip from HBM overlaps the others' work.
+//
+// Whatever does not fit the short way -- inf/NaN in the first part (see hist_tile_raw), more set aside than the
+// list holds, more than kStreamRank candidates in the chosen bin, a bin edge that is not
+// a number -- is left to the two-sweep kernel: the row is marked (`redo`) and the launch that follows handles exactly the marked
+// rows.
+// ------------------------------------------------------------------------------------------------
+constexpr int kStreamBlock = 512;
+constexpr u32 kStreamList = 2048;                    // elements set aside per row, at most
+constexpr u32 kStreamRank = 2 * kStreamBlock - 64;   // candidates ranked directly, at most (two per lane)
+constexpr u32 kStreamWide = kMaxBins + 8;            // words for the copies of the histogram (1 x 4097, 2 x 2049)
+constexpr u32 kStreamChunk = 16;                     // tiles swept between two rounds of fetching the hits
+
+struct SharedStream {
+    union {
+        u32 wide[kStreamWide];              // copies of the first part's histogram (see HistSlot); then the lanes'
+                                            // hit masks of one chunk (16 bits x kStreamBlock x kStreamChunk); then
+                                            // the list's histogram
+        struct {                            // after the last selectBin: the ranking step's arrays
+            uint2 rank_list[2 * kStreamBlock];
+            u64 rank_ext[2 * kStreamBlock];
+        };
+    };
+    uint2 list[kStreamList];                // (raw bits, index) of the elements set aside
+    u32 wsum[kStreamBlock / 64];
+    u32 selv[4];
+    u32 nlist, runW, runC;
+};
+
+// Raw-bit bins visited in key order, with the distrust rule of hist_tile_raw.
+struct RawCounts {
+    const u32* wide;
+    u32 copies, stride, top, mask, first_special;
+    bool largest;
+    __device__ __forceinline__ u32 operator()(u32 keybin, bool* bad) const {
+        const u32 dk = largest ? keybin : mask - keybin;
+        const u32 draw = (dk & top) ? (dk & ~top) : (~dk & mask);  // inverse of key_digit_of_raw
+        u32 c = 0;
+        for (u32 q = 0; q < copies; ++q) c += wide[q * stride + draw];
+        if (c != 0 && (draw & (top - 1u)) >= first_special) *bad = true;
+        return c;
+    }
+};
+
+// One tile of the single sweep: an element is a hit iff it is not below thr (LARGEST; true for a NaN) or below
+// thr (otherwise).  Neither a branch per 64 elements nor much arithmetic per element is affordable here
+// (measured: with either the sweep takes 2-3 times what the row's trip from HBM takes), and hits are too
+// frequent -- one slot in five has some -- to be tested for in bulk.  So the sweep only notes them: every lane
+// shifts one bit per slot into a private mask (compare + add-with-carry) and leaves the mask of the tile's
+// kSlots slots in LDS; the elements are fetched again afterwards, by the same lane, from the caches.
+// Returns the lane's mask: slot s is bit kSlots - 1 - s.
+template <bool FULL, bool LARGEST, class Source, int DT>
+__device__ __forceinline__ u32 stream_tile(const Source& src, const typename Source::Tile& t, float thr) {
+    u32 bits = 0;
+#pragma unroll
+    for (int s = 0; s < Source::kSlots; ++s) {
+        const float x = src.template value<SRC_KEY>(t, s, 0.0f);
+        if (FULL) {
+            // bits = 2 * bits + hit, as compare-into-carry + add-with-carry: two instructions per element (the
+            // compiler's own choice -- select 0/1, shift, or -- is three, and this loop is bound by them)
+            if (LARGEST)
+                asm("v_cmp_ngt_f32 vcc, %1, %2\n\tv_addc_co_u32 %0, vcc, %0, %0, vcc" : "+v"(bits) : "v"(thr), "v"(x) : "vcc");
+            else
+                asm("v_cmp_gt_f32 vcc, %1, %2\n\tv_addc_co_u32 %0, vcc, %0, %0, vcc" : "+v"(bits) : "v"(thr), "v"(x) : "vcc");
+        } else {
+            u32 raw, idx;
+            bool valid;
+            src.get(t, s, raw, idx, valid);
+            const bool hit = (LARGEST ? !(x < thr) : (x < thr)) && valid;
+            bits = bits + bits + (hit ? 1u : 0u);
+        }
+    }
+    return bits;
+}
+
+template <int DT>
+__global__ void __launch_bounds__(kStreamBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) k_row_stream(Params P) {
+    __shared__ SharedStream sm;
+    constexpr int B = kStreamBlock;
+    constexpr bool SINGLE = true;  // (for the diagnostic stamps)
+    typedef KeySource<DT, B, key_vecs<DT>(), false> Source;
+    const int row = blockIdx.x;
+    rtopk_row_trace* st = row_state(P, row);
+    const u32 tid = threadIdx.x, lane = lane_id();
+    RTOPK_STAMP(0);
+    init_row<DT>(P, row, st);
+    Source src;
+    src.init(P.keys, P.n, row);
+    const u32 ntiles = src.ntiles();
+    const DigitCtx ctx = make_digit_ctx(P, 0, 0.0f);
+    const int nb = 1 << ctx.pi.bits;
+    const bool largest = P.dirmask == 0;
+    // copies of the histogram: as many as fit (a power of two, at most 8)
+    const u32 stride = (u32)nb + 1u;
+    u32 copies = 1;
+    while (copies < 8u && 2u * copies * stride <= kStreamWide) copies *= 2u;
+    HistSlot hs{sm.wide + (lane & (copies - 1u)) * stride};
+    RawCounts counts{sm.wide, copies, stride, (u32)nb >> 1, (u32)nb - 1u,
+                     (DT == RTOPK_F16 ? 0x7c000000u : 0x7f800000u) >> ctx.pi.shift, largest};
+    for (u32 j = tid; j < copies * stride; j += B) sm.wide[j] = 0;
+    if (tid == 0) sm.nlist = 0;
+    __syncthreads();
+
+    // ---- countBin on the first part of the row: an eighth of it, more for larger k (about k * row / part
+    // elements will be set aside: keep that near 512), and enough to hold k elements
+    constexpr u32 kTileElems = (u32)B * Source::kSlots;
+    u32 t0 = (ntiles + 7u) / 8u;
+    const u32 by_k = (u32)(((u64)P.k * ntiles + 511u) / 512u);
+    const u32 need = ((u32)P.k + src.lead + kTileElems - 1u) / kTileElems;
+    if (t0 < by_k) t0 = by_k;
+    if (t0 < need) t0 = need;
+    if (t0 > ntiles) t0 = ntiles;
+    auto nothing = []() __attribute__((always_inline)) {};
+    for_each_tile<2>(
+        src, 0u, 1u, ntiles,
+        [&](const typename Source::Tile& cur) { hist_tile_raw<true, Source>(src, cur, ctx, hs); },
+        [&](const typename Source::Tile& cur) { hist_tile_raw<false, Source>(src, cur, ctx, hs); }, 0u, t0);
+    __syncthreads();
+    RTOPK_STAMP(1);
+    u32 why = 0;  // diagnostic: what sent the row to the two-sweep kernel
+    float thr = 0.0f;
+    u32 b0 = 0;
+    {
+        // how many elements have been counted?  (tiles [0, t0) hold elements [0, t0 * tile - lead) of the row)
+        const u64 seen64 = (u64)t0 * kTileElems - src.lead;
+        const u32 seen = seen64 < (u64)P.n ? (u32)seen64 : (u32)P.n;
+        bool distrust = false;
+        Selection s0{};
+        if (seen >= (u32)P.k) s0 = select_from_counts<B>(counts, nb, (u32)P.k, sm, st, nothing, &distrust);
+        b0 = s0.bin;
+        // the bound as a number: set aside what is not below the lower edge of bin b0 ("largest"), or what
+        // is below its upper edge ("smallest": keys are complemented, bin b0 is raw bin maxd - b0)
+        const u32 maxd = (u32)nb - 1u;
+        const u64 Bo = largest ? b0 : maxd - b0;
+        const u64 T = (largest ? Bo : Bo + 1u) << ctx.pi.shift;
+        if (seen < (u32)P.k) why = 2u;
+        else if (distrust) why = 1u;
+        else if (!threshold_number<DT>(T, &thr)) why = 3u;
+        // the part's own share of bins >= b0, scaled to the row, is what the sweep will set aside: give up now
+        // if that will not fit (a wide bin at the edge, say uniform data just below a power of two)
+        else if ((u64)(s0.above + s0.inside) * ntiles > (u64)(kStreamList * 3u / 4u) * t0) why = 7u;
+    }
+    RTOPK_STAMP(2);
+    if (why == 0) {
+        // ---- the sweep, in chunks of kStreamChunk tiles: the sweep notes the hits, then every lane fetches its own
+        static_assert(Source::kSlots == 16, "one 16-bit mask per lane and tile");
+        unsigned short* masks = (unsigned short*)sm.wide;  // [tile in chunk][lane]; the first part's histogram is done with
+        const char* row_bytes = (const char*)P.keys + (size_t)row * (size_t)P.n * KeyOf<DT>::kBytes;
+        for (u32 c0 = 0; c0 < ntiles; c0 += kStreamChunk) {
+            const u32 c1 = c0 + kStreamChunk < ntiles ? c0 + kStreamChunk : ntiles;
+            auto note = [&](const typename Source::Tile& cur, u32 bits) __attribute__((always_inline)) {
+                masks[(cur.tile - c0) * (u32)B + tid] = (unsigned short)bits;
+            };
+            if (largest)
+                for_each_tile<2>(
+                    src, 0u, 1u, ntiles,
+                    [&](const typename Source::Tile& cur) { note(cur, stream_tile<true, true, Source, DT>(src, cur, thr)); },
+                    [&](const typename Source::Tile& cur) { note(cur, stream_tile<false, true, Source, DT>(src, cur, thr)); },
+                    c0, c1);
+            else
+                for_each_tile<2>(
+                    src, 0u, 1u, ntiles,
+                    [&](const typename Source::Tile& cur) { note(cur, stream_tile<true, false, Source, DT>(src, cur, thr)); },
+                    [&](const typename Source::Tile& cur) { note(cur, stream_tile<false, false, Source, DT>(src, cur, thr)); },
+                    c0, c1);
+            if (c0 == 0) RTOPK_STAMP(6);
+            // (each lane reads back only what it wrote itself: no barrier.)  A lane collects up to four hits and
+            // then fetches them together, so that a wave waits for the caches once or twice, not once per hit.
+            u32 h0 = 0, h1 = 0, h2 = 0, h3 = 0, nh = 0;
+            auto fetch = [&]() __attribute__((always_inline)) {
+                auto element = [&](u32 idx) __attribute__((always_inline)) {
+                    return KeyOf<DT>::kBytes == 4 ? ((const u32*)row_bytes)[idx] : (u32)((const unsigned short*)row_bytes)[idx];
+                };
+                const u32 r0 = nh > 0 ? element(h0) : 0u, r1 = nh > 1 ? element(h1) : 0u;
+                const u32 r2 = nh > 2 ? element(h2) : 0u, r3 = nh > 3 ? element(h3) : 0u;
+                const u32 base = nh ? atomicAdd(&sm.nlist, nh) : 0u;
+                if (nh > 0 && base + 0 < kStreamList) sm.list[base + 0] = make_uint2(r0, h0);
+                if (nh > 1 && base + 1 < kStreamList) sm.list[base + 1] = make_uint2(r1, h1);
+                if (nh > 2 && base + 2 < kStreamList) sm.list[base + 2] = make_uint2(r2, h2);
+                if (nh > 3 && base + 3 < kStreamList) sm.list[base + 3] = make_uint2(r3, h3);
+                nh = 0;
+            };
+            for (u32 tl = 0; tl < c1 - c0; ++tl) {
+                u32 m = masks[tl * (u32)B + tid];
+                while (m != 0) {
+                    const u32 bit = 31u - (u32)__builtin_clz(m);
+                    m &= ~(1u << bit);
+                    const u32 slot = 15u - bit;
+                    // element of slot s of tile t for this lane: vector u = s / E of the tile, element j = s % E
+                    constexpr u32 E = Source::E;
+                    const u32 idx = ((c0 + tl) * (u32)Source::kTileVecs + (slot / E) * (u32)B + tid) * E + slot % E - src.lead;
+                    if (nh == 4) fetch();
+                    h3 = h2;
+                    h2 = h1;
+                    h1 = h0;
+                    h0 = idx;
+                    ++nh;
+                }
+            }
+            fetch();
+        }
+        __syncthreads();
+        if (sm.nlist > kStreamList) why = 5u;
+    }
+    RTOPK_STAMP(3);
+    Selection sel{};
+    const u32 nlist = sm.nlist;
+    if (why == 0) {
+        // ---- countBin on the list (exact key digits; all of them are >= b0), then selectBin
+        for (u32 j = tid; j < (u32)nb; j += B) sm.wide[j] = 0;
+        __syncthreads();
+        for (u32 i = tid; i < nlist; i += B) {
+            const uint2 e = sm.list[i];
+            atomicAdd(&sm.wide[digit_of<DT, SRC_KEY>(ctx.pi, e.x, e.y, ctx.dirmask, ctx.idx_max, 0.0f)], 1u);
+        }
+        __syncthreads();
+        sel = select_from_counts<B>(PlainCounts{sm.wide}, nb, (u32)P.k, sm, st,
+                                    [&]() __attribute__((always_inline)) {
+                                        if (tid == 0) {
+                                            sm.runW = 0;
+                                            sm.runC = 0;
+                                        }
+                                    },
+                                    nullptr);
+        if (!sel.emit_all && sel.inside > kStreamRank) why = 6u;
+    }
+    if (why != 0) {
+        if (tid == 0) {
+            st->redo = 1u;
+            st->redo_why = why;
+        }
+        return;
+    }
+    RTOPK_STAMP(4);
+    // ---- selectCandidate + filter on the list (the histogram's memory now holds the ranking arrays)
+    const int bw = sel.emit_all ? (int)sel.bin - 1 : (int)sel.bin;
+    char* out_v = (char*)P.out_values + (size_t)row * (size_t)P.k * KeyOf<DT>::kBytes;
+    long long* out_i = P.out_indices + (size_t)row * (size_t)P.k;
+    for (u32 i = tid; i < nlist; i += B) {
+        const uint2 e = sm.list[i];
+        const u32 d = digit_of<DT, SRC_KEY>(ctx.pi, e.x, e.y, ctx.dirmask, ctx.idx_max, 0.0f);
+        if ((int)d > bw) {
+            const u32 pos = atomicAdd(&sm.runW, 1u);
+            if (pos < (u32)P.k) {
+                store_value<DT>(out_v, pos, e.x);
+                out_i[pos] = (long long)e.y;
+            }
+        } else if (d == sel.bin) {
+            const u32 pos = atomicAdd(&sm.runC, 1u);
+            if (pos < kStreamRank) sm.rank_list[pos] = e;
+        }
+    }
+    const PassEntry e0 = pass_entry(P, st, 0);
+    if (tid == 0) write_pass_record(st, 0, ctx.pi, e0, sel, 4u);
+    if (sel.emit_all) return;
+    __syncthreads();
+    // ---- the ranking step (see rank_finish): C candidates, up to two per lane
+    const u32 C = sel.inside;
+    uint2 mine[2];
+    u64 my[2];
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+        const u32 i = tid + (u32)r * B;
+        mine[r] = make_uint2(0u, 0u);
+        my[r] = 0;
+        if (i < C) {
+            mine[r] = sm.rank_list[i];
+            my[r] = ((u64)(KeyOf<DT>::key(mine[r].x) ^ P.dirmask) << 32) | (u64)(P.idx_max - mine[r].y);
+            sm.rank_ext[i] = my[r];
+        } else if (i < C + 8u) {
+            sm.rank_ext[i] = 0;  // padding: keys that beat nobody
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+        const u32 i = tid + (u32)r * B;
+        if ((i & ~63u) < C) {  // whole waves: the loop's LDS reads are wave-uniform broadcasts
+            u32 rank = 0;
+            for (u32 j = 0; j < C; j += 8) {
+                u64 q[8];
+#pragma unroll
+                for (int z = 0; z < 8; ++z) q[z] = sm.rank_ext[j + z];
+#pragma unroll
+                for (int z = 0; z < 8; ++z) rank += q[z] > my[r] ? 1u : 0u;
+            }
+            if (i < C && rank < sel.k_inside) {
+                const u32 pos = sel.above + rank;
+                if (pos < (u32)P.k) {
+                    store_value<DT>(out_v, pos, mine[r].x);
+                    out_i[pos] = (long long)mine[r].y;
+                }
+            }
+        }
+    }
+    if (tid == 0) {
+        if (sm.runW != sel.above || sm.runC != C) st->error |= 4u;  // the list missed something: never expected
+        st->pass_rec[1].bin = 0;
+        st->pass_rec[1].k_after = 0;
+        st->pass_rec[1].cand_after = 0;
+        st->pass_rec[1].winners = sel.k_inside;
+        st->pass_rec[1].out_before = sel.above;
+        st->pass_rec[1].cand_before = C;
+        st->pass_rec[1].window = SRC_RANK;
+        st->pass_rec[1].where = 4u;
+    }
+    RTOPK_STAMP(5);
+}
+
 static void mark(void* const* events, int i, hipStream_t st) {
     if (events && events[i]) (void)hipEventRecord((hipEvent_t)events[i], st);
 }
@@ -1108,14 +1435,17 @@ static rtopk_status launch_all(const Params& P, const Config& c, bool scaled, hi
         constexpr int kE = 16 / KeyOf<DT>::kBytes;
         const bool aligned = (uintptr_t)P.keys % 16 == 0 && (batch == 1 || P.n % kE == 0);
         const bool resident = P.n + (aligned ? 0 : kE - 1) <= cap;
+        // small k, unscaled: the one-sweep kernel first; the two-sweep kernel then takes the rows it marked
+        const bool one_sweep = c.one_sweep && !scaled;
+        if (one_sweep) hipLaunchKernelGGL((k_row_stream<DT>), dim3(batch), dim3(kStreamBlock), 0, st, P);
         if (resident && scaled)
-            hipLaunchKernelGGL((k_row_resident<DT, kScaledSrc>), dim3(batch), dim3(kRowBlock), 0, st, P);
+            hipLaunchKernelGGL((k_row_resident<DT, kScaledSrc>), dim3(batch), dim3(kRowBlock), 0, st, P, false);
         else if (resident)
-            hipLaunchKernelGGL((k_row_resident<DT, SRC_KEY>), dim3(batch), dim3(kRowBlock), 0, st, P);
+            hipLaunchKernelGGL((k_row_resident<DT, SRC_KEY>), dim3(batch), dim3(kRowBlock), 0, st, P, one_sweep);
         else if (scaled)
-            hipLaunchKernelGGL((k_row<DT, kScaledSrc>), dim3(batch), dim3(kRowBlock), 0, st, P);
+            hipLaunchKernelGGL((k_row<DT, kScaledSrc>), dim3(batch), dim3(kRowBlock), 0, st, P, false);
         else
-            hipLaunchKernelGGL((k_row<DT, SRC_KEY>), dim3(batch), dim3(kRowBlock), 0, st, P);
+            hipLaunchKernelGGL((k_row<DT, SRC_KEY>), dim3(batch), dim3(kRowBlock), 0, st, P, one_sweep);
         mark(events, 4, st);
         return hipGetLastError() == hipSuccess ? RTOPK_OK : RTOPK_ERR_HIP;
     }

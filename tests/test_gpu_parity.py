@@ -52,7 +52,7 @@ def _run_and_check(name, bits, dtype, k, largest=True, scaling=False, seed=0, tu
 SIZES = [1, 2, 63, 64, 65, 1000, 8191, 8192, 8193, 40000, 100003]
 
 
-@pytest.mark.parametrize("path", [1, 2])
+@pytest.mark.parametrize("path", [1, 2, 3])
 @pytest.mark.parametrize("n", SIZES)
 def test_fp32_normal_all_sizes_both_paths(path, n):
     bits = W.normal(n, seed=n).view(np.uint32)
@@ -61,7 +61,7 @@ def test_fp32_normal_all_sizes_both_paths(path, n):
             _run_and_check("normal", bits, F32, k, largest, tuning=dict(path=path))
 
 
-@pytest.mark.parametrize("path", [1, 2])
+@pytest.mark.parametrize("path", [1, 2, 3])
 def test_duplicates_ties_at_kth_key(path):
     bits = W.duplicates(50000, seed=1).view(np.uint32)
     for k in (10, 30000, 49000):
@@ -71,7 +71,7 @@ def test_duplicates_ties_at_kth_key(path):
         _run_and_check("dup smallest", bits, F32, k, False, tuning=dict(path=path, small_threshold=1, wgs_per_row=3))
 
 
-@pytest.mark.parametrize("path", [1, 2])
+@pytest.mark.parametrize("path", [1, 2, 3])
 @pytest.mark.parametrize("d", [8, 11, 12])
 def test_special_values_every_digit_width(path, d):
     bits = W.specials_ramp(30001, seed=2, with_nan=True).view(np.uint32)
@@ -80,7 +80,7 @@ def test_special_values_every_digit_width(path, d):
             _run_and_check("specials", bits, F32, k, largest, tuning=dict(path=path, digit_bits=d))
 
 
-@pytest.mark.parametrize("path", [1, 2])
+@pytest.mark.parametrize("path", [1, 2, 3])
 def test_zero_boundary_and_signed_zero_ties(path):
     # many +0 and -0: the k-th key falls on the boundary where a float comparison cannot replace the key
     n = 70001
@@ -108,7 +108,7 @@ def test_scaling_is_result_neutral(path):
 
 
 @pytest.mark.parametrize("dtype", [F16, BF16])
-@pytest.mark.parametrize("path", [1, 2])
+@pytest.mark.parametrize("path", [1, 2, 3])
 def test_16bit_types(dtype, path):
     n = 50001
     if dtype == F16:
@@ -124,7 +124,7 @@ def test_16bit_types(dtype, path):
         _run_and_check("16-bit scaling flag ignored", bits, dtype, 100, True, scaling=True, tuning=dict(path=path))
 
 
-@pytest.mark.parametrize("path", [1, 2])
+@pytest.mark.parametrize("path", [1, 2, 3])
 def test_batch_with_misaligned_rows(path):
     # odd row lengths: only row 0 starts on a 16-byte boundary
     for dtype, bits in ((BF16, W.llm_logits(9, 4099, 12)), (F32, W.normal(9 * 10007, 13).view(np.uint32).reshape(9, 10007)),
@@ -171,6 +171,57 @@ def test_ranking_step_breaks_ties_by_index_and_leaves_a_record():
         for largest in (True, False):
             _run_and_check("dup ranked", x.view(np.uint32), F32, k, largest, tuning=dict(path=1))
             _run_and_check("dup ranked bf16", W.to_bf16_bits(x), BF16, k, largest, tuning=dict(path=2, small_threshold=1))
+
+
+def test_one_sweep_kernel_and_its_hand_over():
+    # path 3: the one-sweep kernel for small k, with every reason it has to hand a row to the two-sweep kernel.
+    # Rows that went the short way carry the one-sweep kernel's mark (4) in their records.
+    T = dict(path=3)
+    short = lambda tr: all(r.where == 4 for r in tr.passes)
+    # long rows (several chunks of the hit masks), all three types, both directions, odd lengths in a batch
+    x = W.normal(3 * 300001, 41, sigma=3.0)
+    for dtype, bits in ((F32, x.view(np.uint32)), (BF16, W.to_bf16_bits(x)), (F16, x.astype(np.float16).view(np.uint16))):
+        for k in (1, 50, 256):
+            for largest in (True, False):
+                trs = _run_and_check("one sweep long rows", bits.reshape(3, 300001), dtype, k, largest, tuning=T)
+                if dtype == F32:
+                    assert all(short(t) for t in trs)
+    # the benchmark's batch shape, a few rows of it
+    trs = _run_and_check("one sweep logits", W.llm_logits(24, 131072, 42), BF16, 50, True, tuning=T)
+    assert sum(short(t) for t in trs) >= 20
+    # +inf / NaN in the first part of the row: raw-bit bins cannot be trusted
+    y = W.normal(100000, 43)
+    y[7] = np.inf
+    assert not short(_run_and_check("inf first", y.view(np.uint32), F32, 20, True, tuning=T)[0])
+    y[7] = np.nan
+    y[90000] = -np.nan
+    _run_and_check("nan first and last", y.view(np.uint32), F32, 20, True, tuning=T)
+    # NaN / inf only in the swept part: set aside like any large element, no hand-over needed
+    z = W.normal(100000, 44)
+    z[60000], z[70000], z[80000] = np.inf, np.nan, -np.inf
+    for largest in (True, False):
+        _run_and_check("specials late", z.view(np.uint32), F32, 20, largest, tuning=T)
+        _run_and_check("specials late bf16", W.to_bf16_bits(z), BF16, 20, largest, tuning=T)
+    # the k-th key at a zero / the bin edge is not a number
+    q = W.uniform_range(50000, 45, 0.0, 1.0)
+    q[::3] = 0.0
+    q[1::3] = -0.0
+    assert not short(_run_and_check("edge at zero", q.view(np.uint32), F32, 20, False, tuning=T)[0])
+    # everything equal: the whole row would be set aside; many equal keys at the k-th: too many to rank
+    assert not short(_run_and_check("all equal", np.full(60000, np.float32(3.0)).view(np.uint32), F32, 10, True, tuning=T)[0])
+    e = W.normal(80000, 46)
+    e[e > 1.5] = 1.5                        # about 5000 copies of the largest value
+    assert not short(_run_and_check("flat top", e.view(np.uint32), F32, 100, True, tuning=T)[0])
+    # a wide bin at the edge (uniform data just below 1): the early estimate gives the row up
+    _run_and_check("uniform", W.uniform01(65536, 47).view(np.uint32), F32, 32, True, tuning=T)
+    # descending and ascending sorted rows (hits all in one place / nothing learnt from the first part)
+    srt = np.sort(W.normal(70000, 48))
+    for arr in (srt, srt[::-1].copy()):
+        for largest in (True, False):
+            _run_and_check("sorted", arr.view(np.uint32), F32, 64, largest, tuning=T)
+    # k beyond what the automatic choice would send here, and k = n
+    _run_and_check("large k", W.normal(40000, 49).view(np.uint32), F32, 5000, True, tuning=T)
+    _run_and_check("k = n", W.normal(9000, 50).view(np.uint32), F32, 9000, True, tuning=T)
 
 
 def test_batch_many_rows_grid_path():

@@ -62,7 +62,7 @@ def test_workspace_bytes_scales_with_the_candidate_arrays():
 @pytest.mark.parametrize("args", [
     dict(batch=0), dict(n=0), dict(k=0), dict(k=11), dict(dtype=3), dict(dtype=-1), dict(flags=2),
     dict(n=(1 << 31) + 1, k=1),
-    dict(tuning=dict(digit_bits=7)), dict(tuning=dict(digit_bits=13)), dict(tuning=dict(path=3)),
+    dict(tuning=dict(digit_bits=7)), dict(tuning=dict(digit_bits=13)), dict(tuning=dict(path=4)),
     dict(tuning=dict(wgs_per_row=-1)),
 ])
 def test_workspace_bytes_rejects_bad_arguments(args):
