@@ -37,6 +37,7 @@ class RtopkTuning(ctypes.Structure):
         ("path", ctypes.c_int32),
         ("wgs_per_row", ctypes.c_int32),
         ("small_threshold", ctypes.c_int32),
+        ("prefilter", ctypes.c_int32),
     ]
 
 
@@ -58,7 +59,7 @@ class _PassRec(ctypes.Structure):
 
 
 class RtopkRowTrace(ctypes.Structure):
-    _fields_ = [("a_s", ctypes.c_float), ("error", ctypes.c_uint32), ("redo", ctypes.c_uint32), ("redo_why", ctypes.c_uint32), ("reserved", ctypes.c_uint32 * 12),
+    _fields_ = [("a_s", ctypes.c_float), ("error", ctypes.c_uint32), ("redo", ctypes.c_uint32), ("redo_why", ctypes.c_uint32), ("pre_elems", ctypes.c_uint32), ("reserved", ctypes.c_uint32 * 11),
                 ("pass_rec", _PassRec * RTOPK_TRACE_MAX_PASSES)]
 
     @property

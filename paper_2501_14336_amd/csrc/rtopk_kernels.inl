@@ -65,7 +65,7 @@ struct Shared {
     u32 hist[kMaxBins];
     u32 wsum[B / 64];
     u32 red[2 * (B / 64)];
-    u32 selv[4];                      // selectBin's result: bin, count above it, count inside it; distrust flag
+    u32 selv[5];                      // selectBin's result: bin, count above it, count inside it; distrust flag; total
     float a_s;                        // the row's scaling constant, broadcast by the thread that drew it
     u32 runW, runC;                   // next free output / candidate position of this workgroup's range
     union {
@@ -120,6 +120,7 @@ struct Selection {
     u32 above;      // g: candidates in better bins -- certain winners
     u32 inside;     // candidates in bin b
     u32 k_inside;   // rank of the k-th key inside bin b
+    u32 total;      // candidates counted in all bins
     bool emit_all;  // inside == k_inside: the whole bin wins and the row is finished
 };
 
@@ -146,6 +147,7 @@ __device__ __forceinline__ Selection select_from_counts(Count&& count, int nb, u
         s += c[i];
     }
     if (threadIdx.x == 0) sm.selv[0] = sm.selv[1] = sm.selv[2] = sm.selv[3] = 0;
+    // (selv[4], the total, is written by the last thread below: no clearing needed)
     const u32 incl = block_inclusive_scan<B>(s, sm.wsum);
     after_read();
     const u32 before = incl - s;  // candidates in bins above this thread's
@@ -162,13 +164,17 @@ __device__ __forceinline__ Selection select_from_counts(Count&& count, int nb, u
         }
     }
     if (bad) sm.selv[3] = 1u;
-    if (threadIdx.x == B - 1 && !distrust && (k_rem == 0 || k_rem > incl)) st->error |= 1u;  // never expected
+    if (threadIdx.x == B - 1) {
+        sm.selv[4] = incl;
+        if (!distrust && (k_rem == 0 || k_rem > incl)) st->error |= 1u;  // never expected
+    }
     __syncthreads();
     Selection r;
     r.bin = sm.selv[0];
     r.above = sm.selv[1];
     r.inside = sm.selv[2];
     r.k_inside = k_rem - r.above;
+    r.total = sm.selv[4];
     r.emit_all = r.inside == r.k_inside;
     if (distrust) *distrust = sm.selv[3] != 0u;
     return r;
@@ -419,7 +425,13 @@ __device__ __forceinline__ Selection hist_phase(const Source& src, const Params&
         auto edge = [&](const typename Source::Tile& cur) {
             hist_tile<false, true, Source, DT, SRC>(src, cur, ctx, hs, lane);
         };
-        if constexpr (!SINGLE && Source::kStreams) {
+        if (!SINGLE && P.pre_tiles != 0) {
+            // before a prefilter sweep only the row's first part is counted; with ordinary loads as far as the
+            // last-level cache will hold it for the sweep, streamed beyond that
+            const u32 cached = P.pre_tiles < P.pre_cached_tiles ? P.pre_tiles : P.pre_cached_tiles;
+            for_each_tile<2>(src.plain(), wg, G, ntiles, full, edge, 0u, cached);
+            for_each_tile<2>(src, wg, G, ntiles, full, edge, cached, P.pre_tiles);
+        } else if constexpr (!SINGLE && Source::kStreams) {
             // A streamed row: everything but its tail is read with non-temporal loads; the tail is read with
             // ordinary loads and so stays in the last-level cache, where the CLASSIFY sweep finds it (its own
             // loads are all non-temporal and displace nothing on the way there).
@@ -433,11 +445,13 @@ __device__ __forceinline__ Selection hist_phase(const Source& src, const Params&
     if (SINGLE) {
         return select_pass<B>([&](u32 j, bool*) __attribute__((always_inline)) { return copies_of(j); }, nb, e, sm, st);
     } else {
-        u32* ghist = P.ghist + ((size_t)(p % 3) * P.batch + row) * kMaxBins;
+        // (the first part's histogram stands before pass 0: buffer (0 - 1) mod 3; nobody needs its per-workgroup records)
+        u32* ghist = P.ghist + ((size_t)(P.pre_tiles != 0 ? 2 : p % 3) * P.batch + row) * kMaxBins;
         for (int j = tid; j < nb; j += B) {
             u32 c = sm.hist[j];
             if (c) atomicAdd(&ghist[j], c);
         }
+        if (P.pre_tiles != 0) return none;
         suffix_sums_in_place<B>(sm.hist, nb, sm.wsum);
         u32* mine = P.swg + (((size_t)(p & 1) * P.batch + row) * P.G + wg) * kSwgStride;
         for (int j = tid; j < nb; j += B) mine[j] = sm.hist[j];
@@ -496,7 +510,8 @@ __device__ __forceinline__ bool threshold_number(u64 T, float* out) {
 }
 
 // Winner / candidate lane masks of slot s of a tile.
-template <bool FULL, bool FLOATCMP, class Source, int DT, int SRC>
+// PRE (the prefilter sweep): nothing wins yet, and everything whose digit is at least o.b stays a candidate.
+template <bool FULL, bool FLOATCMP, class Source, int DT, int SRC, bool PRE = false>
 __device__ __forceinline__ void slot_masks(const Source& src, const typename Source::Tile& t, int s, const DigitCtx& c,
                                            const ClassifyOut<DT>& o, u64& mw, u64& mc) {
     u64 vm = ~0ull;
@@ -508,14 +523,24 @@ __device__ __forceinline__ void slot_masks(const Source& src, const typename Sou
     }
     if constexpr (FLOATCMP) {
         const float x = src.template value<SRC>(t, s, c.a_s);
-        mw = (ballot64(x < o.t1) ^ o.flip) & vm;
-        mc = (ballot64(x < o.t2) ^ o.flip) & vm & ~mw;
+        if constexpr (PRE) {
+            mw = 0;
+            mc = (ballot64(x < o.t2) ^ o.flip) & vm;
+        } else {
+            mw = (ballot64(x < o.t1) ^ o.flip) & vm;
+            mc = (ballot64(x < o.t2) ^ o.flip) & vm & ~mw;
+        }
     } else {
         u32 dg[Source::E];
         vector_digits<DT, SRC>(src, t, s / Source::E, c, dg);  // shared by the slots of one vector
         const u32 d = dg[s % Source::E];
-        mw = ballot64((int)d > o.bw) & vm;
-        mc = ballot64(d == o.b) & vm & ~mw;
+        if constexpr (PRE) {
+            mw = 0;
+            mc = ballot64(d >= o.b) & vm;
+        } else {
+            mw = ballot64((int)d > o.bw) & vm;
+            mc = ballot64(d == o.b) & vm & ~mw;
+        }
     }
 }
 
@@ -578,7 +603,7 @@ struct WriteState {
 
 // One tile, one sweep over its slots: classify, append survivors to the wave's buffers.
 // RARE: survivors are expected to be few (fully unrolled callers: keeps the append code off the straight path).
-template <bool FULL, bool FLOATCMP, class Source, int DT, int SRC, int B, bool RARE = false>
+template <bool FULL, bool FLOATCMP, class Source, int DT, int SRC, int B, bool RARE = false, bool PRE = false>
 __device__ __forceinline__ void classify_tile(const Source& src, const typename Source::Tile& t, const DigitCtx& c,
                                               const ClassifyOut<DT>& o, Shared<B>& sm, u32 lane, u32 wave,
                                               WriteState& ws, const NextCount& nc) {
@@ -590,7 +615,7 @@ __device__ __forceinline__ void classify_tile(const Source& src, const typename 
 #pragma unroll
     for (int s = 0; s < S; ++s) {
         u64 mw, mc;
-        slot_masks<FULL, FLOATCMP, Source, DT, SRC>(src, t, s, c, o, mw, mc);
+        slot_masks<FULL, FLOATCMP, Source, DT, SRC, PRE>(src, t, s, c, o, mw, mc);
         const bool any = (mw | mc) != 0;
         if (RARE ? __builtin_expect(any, false) : any) {
             u32 raw, idx;
@@ -623,12 +648,17 @@ enum { HIST_IN_LDS = 0, HIST_IN_GLOBAL = 1 };
 // the running write positions).  SINGLE: the row is handled by this workgroup alone (wg = 0, G = 1);
 // otherwise G workgroups share the row.
 // Returns the loop state for pass p + 1 (what the pass record written here says, without the trip through memory).
-template <class Source, int DT, int SRC, int B, bool SINGLE, class Resident = NoResident>
+// PRE: the prefilter sweep over X (many workgroups, first digit): `sel` comes from the histogram of the row's first
+// part only, so its bin is a lower bound of the true one; nothing is written to the output, every element of a
+// bin >= sel.bin goes to the candidate array (into a segment of fixed position: there are no counts to derive
+// exact offsets from), and the digit counted for the next pass is this same first digit.
+template <class Source, int DT, int SRC, int B, bool SINGLE, class Resident = NoResident, bool PRE = false>
 __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Params& P, int p, int row, u32 wg, u32 G,
                                                     const PassEntry& e, rtopk_row_trace* st, float a_s, Shared<B>& sm,
                                                     u32 where, const Selection& sel, u32 records, bool own_segment,
                                                     const Resident& resident = Resident()) {
     constexpr bool kResident = !std::is_same<Resident, NoResident>::value;
+    static_assert(!PRE || (!SINGLE && !kResident && SRC != SRC_RUNTIME), "the prefilter is a grid sweep over X");
     const DigitCtx ctx = make_digit_ctx(P, p, a_s);
     const int nb = 1 << ctx.pi.bits;
     const u32 tid = threadIdx.x;
@@ -640,7 +670,17 @@ __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Par
     unsigned long long t_begin = wall_clock64(), t_pro = 0, t_sweep = 0;
 #endif
     u32 runW = e.out_before, runC = 0, myC = 0;
-    if (!SINGLE) {
+    if constexpr (PRE) {
+        // this workgroup's segment starts where the tiles of the workgroups before it would end if every element
+        // of theirs were kept (tiles are dealt round-robin: workgroup v has ntiles / G of them, one more if
+        // v < ntiles % G)
+        const u32 q = ntiles / G, r = ntiles % G;
+        runC = (wg * q + (wg < r ? wg : r)) * (u32)(B * Source::kSlots);
+        if (wg == 0) {
+            u32* other = P.ghist + ((size_t)1 * P.batch + row) * kMaxBins;  // rotation with p = -1: read 2, fill 0, clear 1
+            for (int j = tid; j < kMaxBins; j += B) other[j] = 0;
+        }
+    } else if (!SINGLE) {
         // exact write offsets: sum, at the chosen bin, the stored suffix sums of the workgroups before this one
         // (`records` workgroups have a record for this pass)
         const u32 upto = wg < records ? wg : records;
@@ -665,25 +705,31 @@ __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Par
             for (int j = tid; j < kMaxBins; j += B) other[j] = 0;
         }
     }
-    if (wg == 0 && tid == 0) write_pass_record(st, p, ctx.pi, e, sel, where);
+    if (!PRE && wg == 0 && tid == 0) {
+        write_pass_record(st, p, ctx.pi, e, sel, where);
+        // after a prefilter the first digit pass looks at what the prefilter kept, not at all of X
+        if (!SINGLE && p == 0 && P.pre_tiles != 0) st->pass_rec[0].cand_before = sel.total;
+    }
 
     // few candidates left and the row is this workgroup's alone: keep them in LDS for the ranking step
     // (which orders by key and index, so every scaled-key digit must have been used by then)
     const bool to_rank = SINGLE && !sel.emit_all && sel.inside <= kRankCap && p + 1 < P.npass &&
                          P.pass[p + 1].src != SRC_SCALED;
     // the next pass: does it exist, and will the many-workgroup kernels run it?
-    const bool count_next = !sel.emit_all && p + 1 < P.npass && !to_rank;
-    const bool next_multi = !SINGLE && count_next && sel.inside > P.small;
-    const PassInfo next_pi = P.pass[p + 1 < P.npass ? p + 1 : p];
+    const bool count_next = PRE || (!sel.emit_all && p + 1 < P.npass && !to_rank);
+    const bool next_multi = PRE || (!SINGLE && count_next && sel.inside > P.small);
+    const PassInfo next_pi = PRE ? P.pass[p] : P.pass[p + 1 < P.npass ? p + 1 : p];
     const int nb_next = 1 << next_pi.bits;
+    // buffers of the "next" pass: p + 1, or p itself after a prefilter (which stands before pass p as pass p - 1)
+    const int pn = PRE ? p : p + 1;
 
     ClassifyOut<DT> o;
     o.out_v = (char*)P.out_values + (size_t)row * (size_t)P.k * KeyOf<DT>::kBytes;
     o.out_i = P.out_indices + (size_t)row * (size_t)P.k;
-    o.cand_out = P.cand[p & 1] + (size_t)row * (size_t)P.n;
+    o.cand_out = P.cand[(pn - 1) & 1] + (size_t)row * P.cand_stride;
     o.cand_lds = to_rank ? (uint2*)sm.hist : nullptr;
     o.kk = (u32)P.k;
-    o.ncap = (u32)P.n;
+    o.ncap = (u32)P.cand_stride;
     o.b = sel.bin;
     o.bw = sel.emit_all ? (int)sel.bin - 1 : (int)sel.bin;
     // First pass over X: the digit is the key's top bits, so "digit > b" and "digit >= b" are comparisons of
@@ -743,15 +789,15 @@ __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Par
         [&](const typename Source::Tile& cur) {
             if constexpr (SRC != SRC_RUNTIME) {
                 if (floatcmp)
-                    classify_tile<true, true, Source, DT, SRC, B>(src, cur, ctx, o, sm, lane, wave, ws, nc);
+                    classify_tile<true, true, Source, DT, SRC, B, false, PRE>(src, cur, ctx, o, sm, lane, wave, ws, nc);
                 else
-                    classify_tile<true, false, Source, DT, SRC, B>(src, cur, ctx, o, sm, lane, wave, ws, nc);
+                    classify_tile<true, false, Source, DT, SRC, B, false, PRE>(src, cur, ctx, o, sm, lane, wave, ws, nc);
             } else {
                 classify_tile<true, false, Source, DT, SRC, B>(src, cur, ctx, o, sm, lane, wave, ws, nc);
             }
         },
         [&](const typename Source::Tile& cur) {
-            classify_tile<false, false, Source, DT, SRC, B>(src, cur, ctx, o, sm, lane, wave, ws, nc);
+            classify_tile<false, false, Source, DT, SRC, B, false, PRE>(src, cur, ctx, o, sm, lane, wave, ws, nc);
         });
     if (ws.fillW) flush_wave_winners<DT>(o, sm.wbuf[wave], &sm.runW, ws.fillW, lane);
     if (ws.fillC) flush_wave_candidates<DT>(o, sm.cbuf[wave], &sm.runC, ws.fillC, lane, nc);
@@ -765,7 +811,7 @@ __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Par
         // next CLASSIFY needs for its offsets, and the segment of the candidate array this workgroup wrote
         __syncthreads();
         if (!SINGLE) {
-            u32* gnext = P.ghist + ((size_t)((p + 1) % 3) * P.batch + row) * kMaxBins;
+            u32* gnext = P.ghist + ((size_t)(pn % 3) * P.batch + row) * kMaxBins;
             for (int j = tid; j < nb_next; j += B) {
                 const u32 c = sm.hist[j];
                 if (c) atomicAdd(&gnext[j], c);
@@ -773,13 +819,13 @@ __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Par
         }
         if (next_multi) suffix_sums_in_place<B>(sm.hist, nb_next, sm.wsum);
         if (next_multi) {
-            u32* mine = P.swg + (((size_t)((p + 1) & 1) * P.batch + row) * P.G + wg) * kSwgStride;
+            u32* mine = P.swg + (((size_t)(pn & 1) * P.batch + row) * P.G + wg) * kSwgStride;
             for (int j = tid; j < nb_next; j += B) mine[j] = sm.hist[j];
             if (tid == 0) {
                 mine[nb_next] = 0;
-                u32* seg = P.seg + (((size_t)(p & 1) * P.batch + row) * P.G + wg) * 2;
+                u32* seg = P.seg + (((size_t)((pn - 1) & 1) * P.batch + row) * P.G + wg) * 2;
                 seg[0] = runC;
-                seg[1] = myC;
+                seg[1] = PRE ? sm.runC - runC : myC;  // (the prefilter learns its count by writing)
             }
         }
     }
@@ -816,7 +862,8 @@ template <int DT>
 __device__ __forceinline__ float init_row(const Params& P, int row, rtopk_row_trace* st) {
     static_assert(sizeof(rtopk_row_trace) / 4 <= 128 && offsetof(rtopk_row_trace, a_s) == 0, "trace layout");
     u32* w = (u32*)st;
-    if (threadIdx.x >= 1 && threadIdx.x < sizeof(rtopk_row_trace) / 4) w[threadIdx.x] = 0;
+    if (threadIdx.x >= 1 && threadIdx.x < sizeof(rtopk_row_trace) / 4 && threadIdx.x != offsetof(rtopk_row_trace, pre_elems) / 4)
+        w[threadIdx.x] = 0;
     float a_s = 0.0f;
     if (threadIdx.x == 0) {
         if (DT == RTOPK_F32 && (P.flags & RTOPK_FLAG_SCALING)) {
@@ -825,6 +872,9 @@ __device__ __forceinline__ float init_row(const Params& P, int row, rtopk_row_tr
             if ((bits & 0x7f800000u) != 0x7f800000u) a_s = __uint_as_float(bits);  // finite only
         }
         st->a_s = a_s;
+        // how much of the row is counted before a prefilter sweep (0: no prefilter)
+        const u64 part = (u64)P.pre_tiles * (u64)(kGridBlock * kHostElemsPerLane);
+        st->pre_elems = part < (u64)P.n ? (u32)part : (P.pre_tiles ? (u32)P.n : 0u);
     }
     return a_s;
 }
@@ -876,7 +926,25 @@ __global__ void __launch_bounds__(kGridBlock) k_classify_keys(Params P) {
                                                               sel, ntiles < gridDim.x ? ntiles : gridDim.x, false);
 }
 
-// Pass p >= 1 on the grid: workgroup w classifies the candidates workgroup w kept in pass p - 1.
+// The prefilter sweep: selectBin on the first part's histogram bounds the row's bin from below; one sweep over X
+// moves everything from that bin upwards into the candidate array and counts its first digit.  Pass 0 then
+// runs on those candidates like any later pass: X is read once (plus its first part a second time, from the
+// caches) instead of twice.
+template <int DT, int SRC, bool NT>
+__global__ void __launch_bounds__(kGridBlock) k_prefilter_keys(Params P) {
+    __shared__ Shared<kGridBlock> sm;
+    const int row = blockIdx.y;
+    rtopk_row_trace* st = row_state(P, row);
+    const PassEntry e = pass_entry(P, st, 0);
+    KeySource<DT, kGridBlock, key_vecs<DT>(), NT> src;
+    src.init(P.keys, P.n, row);
+    const Selection sel = select_pass<kGridBlock>(PlainCounts{global_hist(P, 2, row)}, 1 << P.pass[0].bits, e, sm, st);
+    classify_phase<decltype(src), DT, SRC, kGridBlock, false, NoResident, true>(src, P, 0, row, blockIdx.x, gridDim.x, e, st,
+                                                                                st->a_s, sm, 1u, sel, gridDim.x, false);
+}
+
+// Pass p on the grid (p >= 1, or p = 0 after a prefilter): workgroup w classifies the candidates workgroup w kept
+// in the sweep before.
 template <int DT>
 __global__ void __launch_bounds__(kGridBlock) k_classify_cand(Params P, int p) {
     __shared__ Shared<kGridBlock> sm;
@@ -886,7 +954,7 @@ __global__ void __launch_bounds__(kGridBlock) k_classify_cand(Params P, int p) {
     if (!multi_runs_pass(P, e, p)) return;
     const u32* seg = P.seg + (((size_t)((p - 1) & 1) * P.batch + row) * P.G + blockIdx.x) * 2;
     CandSource<kGridBlock, kVecs> src;
-    src.init(P.cand[(p - 1) & 1] + (size_t)row * (size_t)P.n, seg[0], seg[1]);
+    src.init(P.cand[(p - 1) & 1] + (size_t)row * P.cand_stride, seg[0], seg[1]);
     // its own tiles only: the segment is this workgroup's alone
     const Selection sel = select_pass<kGridBlock>(PlainCounts{global_hist(P, p, row)}, 1 << P.pass[p].bits, e, sm, st);
     classify_phase<decltype(src), DT, SRC_RUNTIME, kGridBlock, false>(src, P, p, row, blockIdx.x, gridDim.x, e, st, st->a_s,
@@ -911,7 +979,7 @@ __device__ __forceinline__ void rank_finish(const Params& P, int row, rtopk_row_
     uint2* list = (uint2*)sm.hist;                    // (raw bits, index)
     u64* ext = (u64*)(sm.hist + 2 * kRankCap);        // extended keys
     if (!e.in_lds) {
-        const uint2* cand = P.cand[(p - 1) & 1] + (size_t)row * (size_t)P.n;
+        const uint2* cand = P.cand[(p - 1) & 1] + (size_t)row * P.cand_stride;
         if (tid < C) list[tid] = cand[tid];
     }
     __syncthreads();
@@ -969,7 +1037,7 @@ __device__ __forceinline__ void finish_row(const Params& P, int row, rtopk_row_t
             return;
         }
         CandSource<kRowBlock, kVecs> src;
-        src.init(P.cand[(p - 1) & 1] + (size_t)row * (size_t)P.n, 0u, e.cand);
+        src.init(P.cand[(p - 1) & 1] + (size_t)row * P.cand_stride, 0u, e.cand);
         const int nb = 1 << P.pass[p].bits;
         const Selection sel = hist_from == HIST_IN_GLOBAL
             ? select_pass<kRowBlock>(PlainCounts{global_hist(P, p, row)}, nb, e, sm, st)
@@ -1131,7 +1199,7 @@ struct SharedStream {
     };
     uint2 list[kStreamList];                // (raw bits, index) of the elements set aside
     u32 wsum[kStreamBlock / 64];
-    u32 selv[4];
+    u32 selv[5];
     u32 nlist, runW, runC;
 };
 
@@ -1453,7 +1521,18 @@ static rtopk_status launch_all(const Params& P, const Config& c, bool scaled, hi
     hipLaunchKernelGGL((k_init<DT>), dim3(batch), dim3(256), 0, st, P);
     mark(events, 1, st);
     const bool nt = (P.flags & kInternalStream) != 0;
-    if (scaled && nt) {
+    if (c.prefilter) {
+        // first part's histogram, then the prefilter sweep (never scaled: make_config)
+        if (nt) {
+            hipLaunchKernelGGL((k_hist_keys<DT, SRC_KEY, true>), grid, block, 0, st, P);
+            mark(events, 2, st);
+            hipLaunchKernelGGL((k_prefilter_keys<DT, SRC_KEY, true>), grid, block, 0, st, P);
+        } else {
+            hipLaunchKernelGGL((k_hist_keys<DT, SRC_KEY, false>), grid, block, 0, st, P);
+            mark(events, 2, st);
+            hipLaunchKernelGGL((k_prefilter_keys<DT, SRC_KEY, false>), grid, block, 0, st, P);
+        }
+    } else if (scaled && nt) {
         hipLaunchKernelGGL((k_hist_keys<DT, kScaledSrc, true>), grid, block, 0, st, P);
         mark(events, 2, st);
         hipLaunchKernelGGL((k_classify_keys<DT, kScaledSrc, true>), grid, block, 0, st, P);
@@ -1471,7 +1550,7 @@ static rtopk_status launch_all(const Params& P, const Config& c, bool scaled, hi
         hipLaunchKernelGGL((k_classify_keys<DT, SRC_KEY, false>), grid, block, 0, st, P);
     }
     mark(events, 3, st);
-    for (int p = 1; p <= c.multi_last && p < c.npass; ++p) {
+    for (int p = c.prefilter ? 0 : 1; p <= c.multi_last && p < c.npass; ++p) {
         hipLaunchKernelGGL((k_classify_cand<DT>), grid, block, 0, st, P, p);
     }
     hipLaunchKernelGGL((k_finish<DT>), dim3(batch), dim3(kRowBlock), 0, st, P);

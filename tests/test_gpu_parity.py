@@ -224,6 +224,39 @@ def test_one_sweep_kernel_and_its_hand_over():
     _run_and_check("k = n", W.normal(9000, 50).view(np.uint32), F32, 9000, True, tuning=T)
 
 
+@pytest.mark.parametrize("G", [0, 3, 7])
+def test_prefilter_sweep(G):
+    # many workgroups per row with the prefilter forced on: histogram of the first part only, one sweep that
+    # keeps the bins from the bound upwards, pass 0 on what was kept
+    T = dict(path=2, prefilter=1, wgs_per_row=G)
+    for n in (1, 65, 8193, 100003, 300001):
+        bits = W.normal(n, seed=60 + n % 13).view(np.uint32)
+        for k in sorted({1, min(n, 50), max(1, n // 2), n}):
+            for largest in (True, False):
+                tr = _run_and_check("prefilter", bits, F32, k, largest, tuning=T)[0]
+                assert tr.pre_elems != 0 and tr.passes[0].cand_before <= n
+    sp = W.specials_ramp(30001, seed=61, with_nan=True).view(np.uint32)
+    for k in (5, 1000, 20000):
+        for largest in (True, False):
+            _run_and_check("prefilter specials", sp, F32, k, largest, tuning=dict(T, small_threshold=1))
+    _run_and_check("prefilter duplicates", W.duplicates(50000, seed=62).view(np.uint32), F32, 30000, True,
+                   tuning=dict(T, small_threshold=1))
+    _run_and_check("prefilter bf16 rows", W.llm_logits(5, 40001, 63), BF16, 50, True, tuning=T)
+    _run_and_check("prefilter f16 rows", W.normal(3 * 8195, 64).astype(np.float16).view(np.uint16).reshape(3, 8195), F16, 17, False,
+                   tuning=T)
+    z = W.uniform_range(70001, 65, -1e6, 1e6)
+    z[::7] = 0.0
+    z[3::7] = -0.0
+    npos = int((z > 0).sum())
+    for k in (npos, npos + 5, npos + 70001 // 7 + 3):
+        for largest in (True, False):
+            _run_and_check("prefilter zero boundary", z.view(np.uint32), F32, k, largest, tuning=T)
+    # with scaling the prefilter stays off (the flag wins)
+    tr = _run_and_check("prefilter vs scaling", W.uniform_range(60000, 66, 128.6, 128.7).view(np.uint32), F32, 512, True,
+                        scaling=True, tuning=T)[0]
+    assert tr.pre_elems == 0
+
+
 def test_batch_many_rows_grid_path():
     bits = W.normal(64 * 20000, 15).view(np.uint32).reshape(64, 20000)
     _run_and_check("batch 64 grid", bits, F32, 333, True, tuning=dict(path=2, small_threshold=16))

@@ -35,7 +35,7 @@ def test_header_constants_match_binding():
     assert int(re.search(r"#define RTOPK_TRACE_STRIDE (\d+)", text).group(1)) == B.RTOPK_TRACE_STRIDE
     assert int(re.search(r"#define RTOPK_TRACE_MAX_PASSES (\d+)", text).group(1)) == B.RTOPK_TRACE_MAX_PASSES
     assert ctypes.sizeof(B.RtopkRowTrace) <= B.RTOPK_TRACE_STRIDE
-    assert ctypes.sizeof(B.RtopkTuning) == 16
+    assert ctypes.sizeof(B.RtopkTuning) == 20
 
 
 def test_status_strings():
@@ -62,7 +62,8 @@ def test_workspace_bytes_scales_with_the_candidate_arrays():
 @pytest.mark.parametrize("args", [
     dict(batch=0), dict(n=0), dict(k=0), dict(k=11), dict(dtype=3), dict(dtype=-1), dict(flags=2),
     dict(n=(1 << 31) + 1, k=1),
-    dict(tuning=dict(digit_bits=7)), dict(tuning=dict(digit_bits=13)), dict(tuning=dict(path=4)),
+    dict(tuning=dict(digit_bits=7)), dict(tuning=dict(digit_bits=13)), dict(tuning=dict(path=4)), dict(tuning=dict(prefilter=2)),
+    dict(tuning=dict(prefilter=-2)),
     dict(tuning=dict(wgs_per_row=-1)),
 ])
 def test_workspace_bytes_rejects_bad_arguments(args):
