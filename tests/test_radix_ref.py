@@ -157,3 +157,34 @@ def test_pass_records_are_consistent():
         k -= above
         assert k == p.k_after and inside == p.candidates_after
         cand = cand[dig == p.bin]
+
+
+# ------------------------------------------------------------------------------------------------
+# the bound the one-sweep kernels rest on: selectBin on a part of a row never overshoots the row's bin, and the
+# elements of the bins from that bound upwards carry the whole top of the row's histogram (Section 2.3.1's
+# selectBin only looks at the bins from the pivot's bin upwards)
+# ------------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("largest", [True, False])
+@pytest.mark.parametrize("dtype,d", [(oracle.F32, 12), (oracle.BF16, 11), (oracle.F16, 11), (oracle.F32, 8)])
+def test_select_bin_on_a_part_bounds_the_row_from_below(dtype, d, largest):
+    width = 32 if dtype == oracle.F32 else 16
+    low, high = width - d, width
+    for seed, bits in enumerate(b for s in range(2) for b in _inputs(dtype, 20000, 200 + s)):
+        keys = R.order_key(bits, dtype, largest)
+        for k in (1, 7, 50, 999):
+            b, _ = R.select_bin(R.count_bin(keys, low, high), k)
+            for part in (k, 2500, 10000, 20000):
+                if part < k:
+                    continue
+                b0, _ = R.select_bin(R.count_bin(keys[:part], low, high), k)
+                assert b0 <= b
+                # what lies in bins >= b0 decides everything: same bin, same pivot rank, and it contains the top k
+                kept = R.get_digit(keys, low, high) >= b0
+                assert R.select_bin(R.count_bin(keys[kept], low, high), k) == R.select_bin(R.count_bin(keys, low, high), k)
+                want_v, want_i = oracle.topk(bits, dtype, k, largest)
+                assert np.all(kept[want_i[0]])
+            # any subset will do, not just a prefix
+            sub = keys[seed::3]
+            if sub.size >= k:
+                assert R.select_bin(R.count_bin(sub, low, high), k)[0] <= b
