@@ -295,6 +295,53 @@ def test_same_set_for_every_tuning_and_repeated_runs():
             assert np.array_equal(got, want)
 
 
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_randomised_shapes_types_and_tunings(seed):
+    # a seeded walk over (type, batch, n, k, direction, value distribution, every tuning knob): whichever kernels
+    # the call ends up in, the selection is the oracle's
+    rng = np.random.default_rng(seed)
+    kinds = {
+        "normal": lambda t, s: W.normal(t, s),
+        "uniform": lambda t, s: W.uniform01(t, s),
+        "duplicates": lambda t, s: W.duplicates(t, s),
+        "narrow": lambda t, s: W.narrow(t, s),
+        "specials": lambda t, s: W.specials_ramp(t, s, with_nan=True),
+        "constant": lambda t, s: np.full(t, 1.5, np.float32),
+        "ascending": lambda t, s: np.arange(t, dtype=np.float32) - t / 3,
+        "descending": lambda t, s: t / 3 - np.arange(t, dtype=np.float32),
+        "five values": lambda t, s: np.floor(W.uniform01(t, s) * 5).astype(np.float32) - 2,
+    }
+    names = sorted(kinds)
+    for case in range(60):
+        dtype = int(rng.integers(0, 3))
+        if rng.integers(0, 3):
+            n, batch = int(2 ** rng.uniform(0, 17)), int(rng.integers(1, 20))
+        else:
+            n, batch = int(2 ** rng.uniform(14, 21)), int(rng.integers(1, 4))
+        k = [1, int(rng.integers(1, min(n, 64) + 1)), int(rng.integers(1, min(n, 1024) + 1)),
+             int(rng.integers(1, n + 1)), max(1, n // 2), n][int(rng.integers(0, 6))]
+        largest = bool(rng.integers(0, 2))
+        tuning = {}
+        if rng.integers(0, 3) == 0:
+            tuning["digit_bits"] = int(rng.integers(8, 13))
+        if rng.integers(0, 2):
+            tuning["path"] = int(rng.integers(1, 4))
+        if rng.integers(0, 3) == 0:
+            tuning["wgs_per_row"] = int(rng.integers(1, 40))
+        if rng.integers(0, 3) == 0:
+            tuning["small_threshold"] = int(2 ** rng.uniform(5, 17))
+        if rng.integers(0, 3) == 0:
+            tuning["prefilter"] = int(rng.integers(-1, 2))
+        scaling = dtype == F32 and rng.integers(0, 5) == 0
+        name = names[int(rng.integers(0, len(names)))]
+        x = np.asarray(kinds[name](batch * n, int(rng.integers(1, 1 << 30))), np.float32)
+        with np.errstate(over="ignore"):   # ramps longer than 65504 become infinities in fp16: more ties
+            bits = (x.view(np.uint32) if dtype == F32 else
+                    x.astype(np.float16).view(np.uint16) if dtype == F16 else W.to_bf16_bits(x)).reshape(batch, n)
+        _run_and_check("walk %d/%d %s" % (seed, case, name), bits, dtype, k, largest, scaling=bool(scaling),
+                       seed=case, tuning=tuning or None)
+
+
 def test_pass_records_match_algorithm_1_model():
     # the chosen bin, the pivot's rank in it and the candidate count of every key-digit pass equal what the
     # step-by-step numpy model of Algorithm 1 computes (oracle/radix_ref.py)
