@@ -318,7 +318,11 @@ struct CandSource {
     u32 count;
     u64 nvec;
 
-    __device__ __forceinline__ void init(const uint2* c, u32 start, u32 count_) {
+    // cap: entries in the array.  The segment is clipped to it, so that counts from an inconsistent run (which
+    // sets the row's error flag elsewhere) can never send a load outside the workspace.
+    __device__ __forceinline__ void init(const uint2* c, u32 start, u32 count_, u32 cap) {
+        if (start > cap) start = cap;
+        if (count_ > cap - start) count_ = cap - start;
         lead = start & 1u;
         base = (const uint4*)(c + (start - lead));
         count = count_;

@@ -550,19 +550,34 @@ __device__ __forceinline__ void slot_masks(const Source& src, const typename Sou
 // global atomic is involved) and writes the buffer out as one burst of consecutive addresses.
 // Which wave gets which part of the workgroup's range depends on timing: the ORDER of the outputs
 // may differ between runs, the selected set does not.
+// The two flush routines are the only out-of-line calls of the sweeps (inlined, every slot of every tile variant
+// would carry a copy).  Everything they need comes in as scalar arguments, LDS addresses as LDS pointers: an
+// argument passed by reference would sit in scratch memory, and each use of it in the loop would be a round
+// trip to memory that also waits for the stores just issued (a 256-entry flush took 7 us that way).
+template <class T>
+using Lds = __attribute__((address_space(3))) T;
+template <class T>
+using Glb = __attribute__((address_space(1))) T;
+
+__device__ __forceinline__ Lds<u64>* lds_words(const uint2* p) { return (Lds<u64>*)p; }
+__device__ __forceinline__ Lds<u32>* lds_word(u32* p) { return (Lds<u32>*)p; }
+
 template <int DT>
-__device__ __noinline__ void flush_wave_winners(const ClassifyOut<DT>& o, const uint2* buf, u32* run, u32 fill,
-                                                   u32 lane) {
+__device__ __noinline__ void flush_wave_winners(void* out_v, long long* out_i, u32 kk, Lds<u64>* buf, Lds<u32>* run,
+                                                   u32 fill, u32 lane) {
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     u32 base = 0;
-    if (lane == 0) base = atomicAdd(run, fill);
+    if (lane == 0) base = __hip_atomic_fetch_add(run, fill, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     base = __builtin_amdgcn_readfirstlane(base);
     for (u32 i = lane; i < fill; i += 64) {
-        const uint2 e = buf[i];
+        const u64 e = buf[i];
         const u32 pos = base + i;
-        if (pos < o.kk) {
-            store_value<DT>(o.out_v, pos, e.x);
-            o.out_i[pos] = (long long)e.y;
+        if (pos < kk) {
+            if (DT == RTOPK_F32)
+                ((Glb<u32>*)out_v)[pos] = (u32)e;
+            else
+                ((Glb<uint16_t>*)out_v)[pos] = (uint16_t)e;
+            ((Glb<long long>*)out_i)[pos] = (long long)(e >> 32);
         }
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -576,24 +591,50 @@ struct NextCount {
     float a_s;
 };
 
+// to_list: the candidates go to the LDS list cand_lds instead of cand_out; count: the next pass's digit, described
+// by (src, shift, bits, dirmask, idx_max, a_s), is counted into the LDS histogram hist.  (Flags, not null tests:
+// an LDS pointer to the start of the workgroup's LDS is the number 0, and a null generic pointer casts to -1.)
 template <int DT>
-__device__ __noinline__ void flush_wave_candidates(const ClassifyOut<DT>& o, const uint2* buf, u32* run, u32 fill,
-                                                   u32 lane, const NextCount& nc) {
+__device__ __noinline__ void flush_wave_candidates(uint2* cand_out, Lds<u64>* cand_lds, u32 ncap, Lds<u64>* buf,
+                                                   Lds<u32>* run, u32 fill, u32 lane, Lds<u32>* hist, u32 src, u32 shift,
+                                                   u32 bits, u32 dirmask, u32 idx_max, float a_s, bool to_list, bool count) {
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     u32 base = 0;
-    if (lane == 0) base = atomicAdd(run, fill);
+    if (lane == 0) base = __hip_atomic_fetch_add(run, fill, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     base = __builtin_amdgcn_readfirstlane(base);
+    const PassInfo pi{src, shift, bits};
     for (u32 i = lane; i < fill; i += 64) {
-        const uint2 e = buf[i];
+        const u64 e = buf[i];
         const u32 pos = base + i;
-        if (o.cand_lds) {
-            if (pos < kRankCap) o.cand_lds[pos] = e;
-        } else if (pos < o.ncap) {
-            o.cand_out[pos] = e;
+        if (to_list) {
+            if (pos < kRankCap) cand_lds[pos] = e;
+        } else if (pos < ncap) {
+            ((Glb<u64>*)cand_out)[pos] = e;
         }
-        if (nc.hist.h) hist_add(nc.hist, digit_of<DT, SRC_RUNTIME>(nc.pi, e.x, e.y, nc.dirmask, nc.idx_max, nc.a_s), lane);
+        if (count) {
+            // as hist_add: the lanes that hold the first active lane's digit share one LDS atomic
+            const u32 dg = digit_of<DT, SRC_RUNTIME>(pi, (u32)e, (u32)(e >> 32), dirmask, idx_max, a_s);
+            const u32 d0 = __builtin_amdgcn_readfirstlane(dg);
+            const bool same = dg == d0;
+            const u64 m = ballot64(same);
+            const bool leader = lane == (u32)__builtin_ctzll(m);
+            if (!same || leader)
+                __hip_atomic_fetch_add(hist + dg, same ? (u32)__popcll(m) : 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+}
+
+template <int DT>
+__device__ __forceinline__ void flush_winners(const ClassifyOut<DT>& o, const uint2* buf, u32* run, u32 fill, u32 lane) {
+    flush_wave_winners<DT>(o.out_v, o.out_i, o.kk, lds_words(buf), lds_word(run), fill, lane);
+}
+template <int DT>
+__device__ __forceinline__ void flush_candidates(const ClassifyOut<DT>& o, const uint2* buf, u32* run, u32 fill, u32 lane,
+                                                 const NextCount& nc) {
+    flush_wave_candidates<DT>(o.cand_out, lds_words(o.cand_lds), o.ncap, lds_words(buf), lds_word(run), fill, lane,
+                              lds_word(nc.hist.h), nc.pi.src, nc.pi.shift, nc.pi.bits, nc.dirmask, nc.idx_max, nc.a_s,
+                              o.cand_lds != nullptr, nc.hist.h != nullptr);
 }
 
 // Entries waiting in this wave's LDS buffers (wave-uniform).
@@ -625,7 +666,7 @@ __device__ __forceinline__ void classify_tile(const Source& src, const typename 
                 if (mw & me_bit) wbuf[ws.fillW + mbcnt64(mw)] = make_uint2(raw, idx);
                 ws.fillW += (u32)__popcll(mw);
                 if (ws.fillW > (u32)(kStageCap - 64)) {
-                    flush_wave_winners<DT>(o, wbuf, &sm.runW, ws.fillW, lane);
+                    flush_winners<DT>(o, wbuf, &sm.runW, ws.fillW, lane);
                     ws.fillW = 0;
                 }
             }
@@ -633,7 +674,7 @@ __device__ __forceinline__ void classify_tile(const Source& src, const typename 
                 if (mc & me_bit) cbuf[ws.fillC + mbcnt64(mc)] = make_uint2(raw, idx);
                 ws.fillC += (u32)__popcll(mc);
                 if (ws.fillC > (u32)(kStageCap - 64)) {
-                    flush_wave_candidates<DT>(o, cbuf, &sm.runC, ws.fillC, lane, nc);
+                    flush_candidates<DT>(o, cbuf, &sm.runC, ws.fillC, lane, nc);
                     ws.fillC = 0;
                 }
             }
@@ -799,8 +840,8 @@ __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Par
         [&](const typename Source::Tile& cur) {
             classify_tile<false, false, Source, DT, SRC, B, false, PRE>(src, cur, ctx, o, sm, lane, wave, ws, nc);
         });
-    if (ws.fillW) flush_wave_winners<DT>(o, sm.wbuf[wave], &sm.runW, ws.fillW, lane);
-    if (ws.fillC) flush_wave_candidates<DT>(o, sm.cbuf[wave], &sm.runC, ws.fillC, lane, nc);
+    if (ws.fillW) flush_winners<DT>(o, sm.wbuf[wave], &sm.runW, ws.fillW, lane);
+    if (ws.fillC) flush_candidates<DT>(o, sm.cbuf[wave], &sm.runC, ws.fillC, lane, nc);
 
 #ifdef RTOPK_TIMING
     t_sweep = wall_clock64();
@@ -950,11 +991,14 @@ __global__ void __launch_bounds__(kGridBlock) k_classify_cand(Params P, int p) {
     __shared__ Shared<kGridBlock> sm;
     const int row = blockIdx.y;
     rtopk_row_trace* st = row_state(P, row);
+#ifdef RTOPK_TIMING
+    if (p == 0 && threadIdx.x == 0) P.dbg[((size_t)row * P.G + blockIdx.x) * 16 + 5] = wall_clock64();
+#endif
     const PassEntry e = pass_entry(P, st, p);
     if (!multi_runs_pass(P, e, p)) return;
     const u32* seg = P.seg + (((size_t)((p - 1) & 1) * P.batch + row) * P.G + blockIdx.x) * 2;
     CandSource<kGridBlock, kVecs> src;
-    src.init(P.cand[(p - 1) & 1] + (size_t)row * P.cand_stride, seg[0], seg[1]);
+    src.init(P.cand[(p - 1) & 1] + (size_t)row * P.cand_stride, seg[0], seg[1], (u32)P.cand_stride);
     // its own tiles only: the segment is this workgroup's alone
     const Selection sel = select_pass<kGridBlock>(PlainCounts{global_hist(P, p, row)}, 1 << P.pass[p].bits, e, sm, st);
     classify_phase<decltype(src), DT, SRC_RUNTIME, kGridBlock, false>(src, P, p, row, blockIdx.x, gridDim.x, e, st, st->a_s,
@@ -1037,7 +1081,7 @@ __device__ __forceinline__ void finish_row(const Params& P, int row, rtopk_row_t
             return;
         }
         CandSource<kRowBlock, kVecs> src;
-        src.init(P.cand[(p - 1) & 1] + (size_t)row * P.cand_stride, 0u, e.cand);
+        src.init(P.cand[(p - 1) & 1] + (size_t)row * P.cand_stride, 0u, e.cand, (u32)P.cand_stride);
         const int nb = 1 << P.pass[p].bits;
         const Selection sel = hist_from == HIST_IN_GLOBAL
             ? select_pass<kRowBlock>(PlainCounts{global_hist(P, p, row)}, nb, e, sm, st)
