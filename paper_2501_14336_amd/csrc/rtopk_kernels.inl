@@ -1389,7 +1389,8 @@ __global__ void __launch_bounds__(kStreamBlock) __attribute__((amdgpu_waves_per_
             u32 h0 = 0, h1 = 0, h2 = 0, h3 = 0, nh = 0;
             auto fetch = [&]() __attribute__((always_inline)) {
                 auto element = [&](u32 idx) __attribute__((always_inline)) {
-                    return KeyOf<DT>::kBytes == 4 ? ((const u32*)row_bytes)[idx] : (u32)((const unsigned short*)row_bytes)[idx];
+                    return KeyOf<DT>::kBytes == 4 ? ((const Glb<u32>*)row_bytes)[idx]
+                                                  : (u32)((const Glb<unsigned short>*)row_bytes)[idx];
                 };
                 const u32 r0 = nh > 0 ? element(h0) : 0u, r1 = nh > 1 ? element(h1) : 0u;
                 const u32 r2 = nh > 2 ? element(h2) : 0u, r3 = nh > 3 ? element(h3) : 0u;
