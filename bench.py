@@ -109,12 +109,15 @@ def main() -> int:
     es = 4
     prefilter = tr.pre_elems != 0
     if prefilter:
-        # histogram of the row's first part, then ONE sweep over X that keeps `kept` candidates; pass 0 runs on them
-        kept = p0.cand_before
+        # histogram of a sample of the row, then ONE sweep over X that counts every digit and keeps `kept`
+        # candidates; pass 0 runs on them (or, had the sample misled, sweeps X again: not on this input)
+        kept = tr.pre_kept
         hist_bytes = es * tr.pre_elems
         sweep_bytes = es * n + 8 * kept
         later = sum(8 * p.cand_before + 8 * p.cand_after + (es + 8) * p.winners for p in tr.passes)
-        names = ("hist_keys_first_part", "prefilter_keys")
+        if tr.pre_missed:
+            later += (es - 8) * n
+        names = ("hist_keys_sample", "prefilter_keys")
     else:
         hist_bytes = es * n                                               # first-pass HIST reads X once
         sweep_bytes = es * n + 8 * p0.cand_after + (es + 8) * p0.winners  # reads X, writes candidates + winners
@@ -123,6 +126,7 @@ def main() -> int:
     classify_ms, classify_bytes = classify_ms, sweep_bytes
     path_bytes = hist_bytes + sweep_bytes + later                     # every pass, as executed
     floor_bytes = 2 * es * n + (es + 8) * k                           # two sweeps + the output
+    floor1_bytes = es * n + (es + 8) * k                              # X read once + the output
     dominant = (names[1], classify_ms, classify_bytes) if classify_ms >= hist_ms else \
                (names[0], hist_ms, hist_bytes)
     achieved = dominant[2] / (dominant[1] * 1e-3) / 1e9
@@ -158,6 +162,9 @@ def main() -> int:
                        "prefilter": prefilter, "elements_counted_before_the_sweep": tr.pre_elems if prefilter else n,
                        "bytes_moved_by_all_passes": path_bytes,
                        "achieved_frac_of_hbm_peak": path_bytes / (call_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                       "sample_misled": bool(tr.pre_missed) if prefilter else None,
+                       "one_read_floor_bytes": floor1_bytes,
+                       "one_read_floor_frac_of_hbm_peak": floor1_bytes / (call_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                        "two_sweep_floor_bytes": floor_bytes,
                        "two_sweep_floor_frac_of_hbm_peak": floor_bytes / (call_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                        "passes": [[p.where, p.cand_before, p.cand_after, p.winners] for p in tr.passes]},

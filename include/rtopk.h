@@ -66,9 +66,10 @@ typedef struct {
                                 large batches of rows with k <= 256)                                            */
     int32_t wgs_per_row;     /* workgroups cooperating on one row in path 2 (default: fill 256 CUs)            */
     int32_t small_threshold; /* candidate count at or below which one workgroup finishes a row by itself       */
-    int32_t prefilter;       /* path 2: 0 auto, 1 always, -1 never: histogram of the row's first part only, then
-                                ONE sweep over X that keeps everything from the bounded bin upwards (pass 0 then
-                                runs on those candidates) instead of two sweeps over X                          */
+    int32_t prefilter;       /* path 2: 0 auto, 1 always, -1 never: histogram of a sample of the row, then ONE
+                                sweep over X that counts every digit and keeps everything from a bin chosen
+                                from the sample upwards (pass 0 then runs on what was kept), instead of two
+                                sweeps over X; the second sweep still runs if the sample misled               */
 } rtopk_tuning;
 
 /*
@@ -147,9 +148,14 @@ typedef struct {
     uint32_t redo_why;         /* diagnostic, with redo: 1 inf/NaN in the first part, 2 first part
                                   shorter than k, 3 bin edge not a number, 5 list full, 6 too many
                                   candidates in the chosen bin, 7 list expected to overflow           */
-    uint32_t pre_elems;        /* elements of the row counted before a prefilter sweep (0: no prefilter:
-                                  the whole row was counted)                                         */
-    uint32_t reserved[11];
+    uint32_t pre_elems;        /* elements in the row's sample, counted before a prefilter sweep
+                                  (0: no prefilter, the whole row was counted)                       */
+    uint32_t pre_bound;        /* with a prefilter: the bin taken from the sample; the sweep kept the
+                                  elements of this bin and the better ones                           */
+    uint32_t pre_kept;         /* how many elements that were                                        */
+    uint32_t pre_missed;       /* 1: the k-th key's bin lies below pre_bound (the sample misled), so
+                                  pass 0 swept the row again instead of reading what was kept        */
+    uint32_t reserved[8];
     struct {
         uint32_t where;        /* 0 pass not run; 1 many workgroups; 2 single-workgroup finish;
                                   3 fused one-workgroup-per-row kernel; 4 one-sweep row kernel       */

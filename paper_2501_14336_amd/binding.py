@@ -59,7 +59,7 @@ class _PassRec(ctypes.Structure):
 
 
 class RtopkRowTrace(ctypes.Structure):
-    _fields_ = [("a_s", ctypes.c_float), ("error", ctypes.c_uint32), ("redo", ctypes.c_uint32), ("redo_why", ctypes.c_uint32), ("pre_elems", ctypes.c_uint32), ("reserved", ctypes.c_uint32 * 11),
+    _fields_ = [("a_s", ctypes.c_float), ("error", ctypes.c_uint32), ("redo", ctypes.c_uint32), ("redo_why", ctypes.c_uint32), ("pre_elems", ctypes.c_uint32), ("pre_bound", ctypes.c_uint32), ("pre_kept", ctypes.c_uint32), ("pre_missed", ctypes.c_uint32), ("reserved", ctypes.c_uint32 * 8),
                 ("pass_rec", _PassRec * RTOPK_TRACE_MAX_PASSES)]
 
     @property

@@ -55,27 +55,20 @@ static rtopk_status make_config(int64_t batch, int64_t n, int64_t k, rtopk_dtype
     const int eb = elem_bytes(dt);
     const int64_t tile_elems = (int64_t)kHostGridBlock * kHostElemsPerLane;  // 16 elements per lane for every type
     const int64_t ntiles = (n + 16 / eb - 1 + tile_elems) / tile_elems;  // one spare for the lead-in
-    // Prefilter (many workgroups per row, unscaled): count only the row's first part, bound the bin from below,
-    // and sweep X once.  It pays for k well below n (the part is an eighth of the row up to k = n / 1024 and grows
-    // to half of it at k = n / 256); the extra launch is not worth it on small inputs.
+    // Prefilter (many workgroups per row, unscaled): count a sample of the row (every 32nd tile), take from it a
+    // bin that very probably lies at or below the k-th key's, and sweep X ONCE, counting every element's digit
+    // and keeping the elements from that bin upwards; pass 0 then runs on what was kept.  If the full counts
+    // show the bin was too high, the ordinary second sweep over X runs instead (one idle launch otherwise).
+    // It pays while k is well below n (what is kept is written out and read again).
     c->prefilter = false;
-    c->pre_tiles = 0;
+    c->pre_stride = 0;
     if (tn && (tn->prefilter < -1 || tn->prefilter > 1)) return RTOPK_ERR_INVALID_ARG;
     const int pre_knob = tn ? tn->prefilter : 0;
     const bool scaling_on = (flags & RTOPK_FLAG_SCALING) && dt == RTOPK_F32;
     if (path == 2 && !scaling_on &&
-        (pre_knob == 1 || (pre_knob == 0 && batch * n * eb >= ((int64_t)256 << 20) && k <= n / 256))) {
-        int64_t part = (ntiles + 7) / 8;
-        // The bound is as good as the part is large: about k * row / part elements lie above it, and whole bins
-        // are kept (n = 2^28 uniform, k = 2^20: 4.1 % of the row kept with parts up to 0.39 of the row, 0.85 %
-        // from 0.5 on; the call takes 436-477 us and 413 us; two sweeps take 457 us).
-        const int64_t by_k = (128 * k * ntiles + n - 1) / n;
-        const int64_t need = (k + 16 / eb + tile_elems - 1) / tile_elems + 1;  // the part must hold k elements
-        if (part < by_k) part = by_k;
-        if (part < need) part = need;
-        if (part > ntiles) part = ntiles;
+        (pre_knob == 1 || (pre_knob == 0 && batch * n * eb >= ((int64_t)256 << 20) && k <= n / 32))) {
         c->prefilter = true;
-        c->pre_tiles = (unsigned)part;
+        c->pre_stride = 32;
     }
     if (path == 2) {
         if (G == 0) {
@@ -225,8 +218,7 @@ rtopk_status rtopk_select_events(const void* keys, int64_t batch, int64_t n, int
     P.cand[0] = (uint2*)(ws + L.cand0_off);
     P.cand[1] = (uint2*)(ws + L.cand1_off);
     P.cand_stride = L.cand_stride;
-    P.pre_tiles = c.prefilter ? c.pre_tiles : 0u;
-    P.pre_cached_tiles = (u32)(((size_t)224 << 20) / ((size_t)kHostGridBlock * kHostElemsPerLane * eb * (size_t)batch));
+    P.pre_stride = c.prefilter ? c.pre_stride : 0u;
     P.n = n;
     P.k = k;
     P.batch = (int)batch;

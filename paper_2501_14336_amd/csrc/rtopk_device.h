@@ -44,8 +44,7 @@ struct Params {
     int npass;
     u32 flags;               // RTOPK_FLAG_* | kInternalStream
     u32 keep_from_tile;      // streamed inputs: the first sweep reads tiles from this one on with ordinary loads
-    u32 pre_tiles;           // 0, or: a prefilter sweep stands before pass 0 and the row's first part is this many tiles
-    u32 pre_cached_tiles;    // how many of them to read with ordinary loads (what the last-level cache can keep)
+    u32 pre_stride;          // 0, or: a prefilter sweep stands before pass 0; a row's sample is every pre_stride-th full tile
     size_t cand_stride;      // entries per row of the candidate arrays
     u64 seed;
     PassInfo pass[kMaxPasses];

@@ -12,8 +12,8 @@ struct Config {
     u32 small;
     int npass;
     bool one_sweep;  // path 1: try the one-sweep kernel (small k) first
-    bool prefilter;  // path 2: first-part histogram + prefilter sweep instead of two sweeps over X
-    unsigned pre_tiles;
+    bool prefilter;  // path 2: histogram of a sample + ONE sweep over X that counts and filters, instead of two sweeps
+    unsigned pre_stride;
     int multi_last;  // last digit pass that may still hold more than `small` candidates (grid kernels run up to it)
     u32 idx_max, dirmask;
     PassInfo pass[kMaxPasses];

@@ -316,6 +316,30 @@ __device__ __forceinline__ u32 key_digit_of_raw(u32 draw, u32 bits, bool largest
     return largest ? dk : mask - dk;
 }
 
+// The sample of a row that is counted before a prefilter sweep: full tiles first, first + stride, ... (spread
+// over the row, so that a trend along the row does not mislead), and the rank in the sample whose bin the sweep
+// takes as its bound.  The k-th key of the row is expected near rank k * elems / n of the sample; the margin
+// (an eighth, eight standard deviations of a binomial count, and 16) makes a bound above the k-th key's bin
+// rare, and such a miss costs a second sweep, never the result.
+struct RowSample {
+    u32 first, stride, tiles, elems;
+    u64 rank;
+    __device__ __forceinline__ u32 tile(u32 j) const { return first + j * stride; }
+};
+template <class Source>
+__device__ __forceinline__ RowSample row_sample(const Source& src, const Params& P) {
+    RowSample r;
+    u32 f0, f1;
+    src.full_range(f0, f1);
+    r.first = f0;
+    r.stride = P.pre_stride;
+    r.tiles = (f1 - f0 + r.stride - 1u) / r.stride;
+    r.elems = r.tiles * (u32)(Source::kTileVecs * Source::E);
+    const u64 ks = ((u64)P.k * r.elems + (u64)P.n - 1u) / (u64)P.n;
+    r.rank = ks + ks / 8u + 8u * ((u64)sqrtf((float)ks) + 2u) + 16u;
+    return r;
+}
+
 // `Resident`: NoResident, or a callable r(f) that calls f(tile) for every tile of a row the workgroup
 // holds (or is receiving) in registers.
 struct NoResident {};
@@ -425,12 +449,27 @@ __device__ __forceinline__ Selection hist_phase(const Source& src, const Params&
         auto edge = [&](const typename Source::Tile& cur) {
             hist_tile<false, true, Source, DT, SRC>(src, cur, ctx, hs, lane);
         };
-        if (!SINGLE && P.pre_tiles != 0) {
-            // before a prefilter sweep only the row's first part is counted; with ordinary loads as far as the
-            // last-level cache will hold it for the sweep, streamed beyond that
-            const u32 cached = P.pre_tiles < P.pre_cached_tiles ? P.pre_tiles : P.pre_cached_tiles;
-            for_each_tile<2>(src.plain(), wg, G, ntiles, full, edge, 0u, cached);
-            for_each_tile<2>(src, wg, G, ntiles, full, edge, cached, P.pre_tiles);
+        if (!SINGLE && P.pre_stride != 0) {
+            // before a prefilter sweep only a sample of the row is counted: every pre_stride-th full tile
+            const RowSample sample = row_sample(src, P);
+            typename Source::Tile a, b;
+            const auto plain = src.plain();
+            u32 j = wg;
+            if (j < sample.tiles) {
+                plain.load_full(sample.tile(j), tid, a);
+                for (;;) {
+                    const bool more_b = j + G < sample.tiles;
+                    if (more_b) plain.load_full(sample.tile(j + G), tid, b);
+                    full(a);
+                    if (!more_b) break;
+                    const bool more_a = j + 2 * G < sample.tiles;
+                    if (more_a) plain.load_full(sample.tile(j + 2 * G), tid, a);
+                    full(b);
+                    if (!more_a) break;
+                    j += 2 * G;
+                }
+            }
+            if (wg == 0 && tid == 0) st->pre_elems = sample.elems;
         } else if constexpr (!SINGLE && Source::kStreams) {
             // A streamed row: everything but its tail is read with non-temporal loads; the tail is read with
             // ordinary loads and so stays in the last-level cache, where the CLASSIFY sweep finds it (its own
@@ -445,13 +484,13 @@ __device__ __forceinline__ Selection hist_phase(const Source& src, const Params&
     if (SINGLE) {
         return select_pass<B>([&](u32 j, bool*) __attribute__((always_inline)) { return copies_of(j); }, nb, e, sm, st);
     } else {
-        // (the first part's histogram stands before pass 0: buffer (0 - 1) mod 3; nobody needs its per-workgroup records)
-        u32* ghist = P.ghist + ((size_t)(P.pre_tiles != 0 ? 2 : p % 3) * P.batch + row) * kMaxBins;
+        // (the sample's histogram stands before pass 0: buffer (0 - 1) mod 3; nobody needs its per-workgroup records)
+        u32* ghist = P.ghist + ((size_t)(P.pre_stride != 0 ? 2 : p % 3) * P.batch + row) * kMaxBins;
         for (int j = tid; j < nb; j += B) {
             u32 c = sm.hist[j];
             if (c) atomicAdd(&ghist[j], c);
         }
-        if (P.pre_tiles != 0) return none;
+        if (P.pre_stride != 0) return none;
         suffix_sums_in_place<B>(sm.hist, nb, sm.wsum);
         u32* mine = P.swg + (((size_t)(p & 1) * P.batch + row) * P.G + wg) * kSwgStride;
         for (int j = tid; j < nb; j += B) mine[j] = sm.hist[j];
@@ -511,30 +550,31 @@ __device__ __forceinline__ bool threshold_number(u64 T, float* out) {
 
 // Winner / candidate lane masks of slot s of a tile.
 // PRE (the prefilter sweep): nothing wins yet, and everything whose digit is at least o.b stays a candidate.
-template <bool FULL, bool FLOATCMP, class Source, int DT, int SRC, bool PRE = false>
+template <bool FULL, bool FLOATCMP, class Source, int DT, int SRC, bool PRE = false, bool MERGE = false>
 __device__ __forceinline__ void slot_masks(const Source& src, const typename Source::Tile& t, int s, const DigitCtx& c,
-                                           const ClassifyOut<DT>& o, u64& mw, u64& mc) {
+                                           const ClassifyOut<DT>& o, u64& mw, u64& mc, const HistSlot& count = HistSlot{nullptr},
+                                           u32 lane = 0) {
+    static_assert(!(PRE && FLOATCMP), "the prefilter sweep counts digits, so it needs them");
     u64 vm = ~0ull;
+    bool valid = true;
     if (!FULL) {
         u32 raw, idx;
-        bool valid;
         src.get(t, s, raw, idx, valid);
         vm = ballot64(valid);
     }
     if constexpr (FLOATCMP) {
         const float x = src.template value<SRC>(t, s, c.a_s);
-        if constexpr (PRE) {
-            mw = 0;
-            mc = (ballot64(x < o.t2) ^ o.flip) & vm;
-        } else {
-            mw = (ballot64(x < o.t1) ^ o.flip) & vm;
-            mc = (ballot64(x < o.t2) ^ o.flip) & vm & ~mw;
-        }
+        mw = (ballot64(x < o.t1) ^ o.flip) & vm;
+        mc = (ballot64(x < o.t2) ^ o.flip) & vm & ~mw;
     } else {
         u32 dg[Source::E];
         vector_digits<DT, SRC>(src, t, s / Source::E, c, dg);  // shared by the slots of one vector
         const u32 d = dg[s % Source::E];
         if constexpr (PRE) {
+            // countBin of pass 0 for every element of X, and the filter: keep what lies in bin o.b or a better one
+            if (FULL || valid) {
+                if (MERGE) hist_add(count, d, lane); else hist_add_plain(count, d);
+            }
             mw = 0;
             mc = ballot64(d >= o.b) & vm;
         } else {
@@ -644,7 +684,8 @@ struct WriteState {
 
 // One tile, one sweep over its slots: classify, append survivors to the wave's buffers.
 // RARE: survivors are expected to be few (fully unrolled callers: keeps the append code off the straight path).
-template <bool FULL, bool FLOATCMP, class Source, int DT, int SRC, int B, bool RARE = false, bool PRE = false>
+template <bool FULL, bool FLOATCMP, class Source, int DT, int SRC, int B, bool RARE = false, bool PRE = false,
+          bool MERGE = false>
 __device__ __forceinline__ void classify_tile(const Source& src, const typename Source::Tile& t, const DigitCtx& c,
                                               const ClassifyOut<DT>& o, Shared<B>& sm, u32 lane, u32 wave,
                                               WriteState& ws, const NextCount& nc) {
@@ -653,10 +694,14 @@ __device__ __forceinline__ void classify_tile(const Source& src, const typename 
     uint2* wbuf = sm.wbuf[wave];
     uint2* cbuf = sm.cbuf[wave];
     const u64 me_bit = 1ull << lane;
+    // (the prefilter sweep counts every element; MERGE: lanes that share the first lane's digit merge their adds)
 #pragma unroll
     for (int s = 0; s < S; ++s) {
         u64 mw, mc;
-        slot_masks<FULL, FLOATCMP, Source, DT, SRC, PRE>(src, t, s, c, o, mw, mc);
+        if constexpr (PRE)
+            slot_masks<FULL, FLOATCMP, Source, DT, SRC, PRE, MERGE>(src, t, s, c, o, mw, mc, HistSlot{sm.hist}, lane);
+        else
+            slot_masks<FULL, FLOATCMP, Source, DT, SRC, PRE>(src, t, s, c, o, mw, mc);
         const bool any = (mw | mc) != 0;
         if (RARE ? __builtin_expect(any, false) : any) {
             u32 raw, idx;
@@ -749,7 +794,7 @@ __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Par
     if (!PRE && wg == 0 && tid == 0) {
         write_pass_record(st, p, ctx.pi, e, sel, where);
         // after a prefilter the first digit pass looks at what the prefilter kept, not at all of X
-        if (!SINGLE && p == 0 && P.pre_tiles != 0) st->pass_rec[0].cand_before = sel.total;
+        if (!SINGLE && SRC == SRC_RUNTIME && p == 0) st->pass_rec[0].cand_before = st->pre_kept;
     }
 
     // few candidates left and the row is this workgroup's alone: keep them in LDS for the ranking step
@@ -778,7 +823,7 @@ __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Par
     bool floatcmp = false;
     o.t1 = o.t2 = 0.0f;
     o.flip = 0;
-    if constexpr (SRC != SRC_RUNTIME) {
+    if constexpr (SRC != SRC_RUNTIME && !PRE) {
         const bool largest = P.dirmask == 0;
         const u32 maxd = (1u << ctx.pi.bits) - 1u;
         const u64 Bo = largest ? sel.bin : maxd - sel.bin;  // the chosen bin in the uncomplemented key domain
@@ -811,7 +856,7 @@ __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Par
     WriteState ws;
     ws.fillW = ws.fillC = 0;
     NextCount nc;
-    nc.hist = HistSlot{count_next ? sm.hist : nullptr};
+    nc.hist = HistSlot{count_next && !PRE ? sm.hist : nullptr};  // (the prefilter counts in the sweep, every element)
     nc.pi = next_pi;
     nc.dirmask = ctx.dirmask;
     nc.idx_max = ctx.idx_max;
@@ -828,17 +873,23 @@ __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Par
     for_each_tile<SINGLE ? 1 : 2>(
         src, own_segment ? 0u : wg, own_segment ? 1u : G, ntiles,
         [&](const typename Source::Tile& cur) {
-            if constexpr (SRC != SRC_RUNTIME) {
-                if (floatcmp)
-                    classify_tile<true, true, Source, DT, SRC, B, false, PRE>(src, cur, ctx, o, sm, lane, wave, ws, nc);
+            if constexpr (PRE) {
+                // merged adds when the tile's digits are seen to pile up, as in the HIST sweep
+                if (hot_lanes<Source, DT, SRC>(src, cur, ctx) >= 12u)
+                    classify_tile<true, false, Source, DT, SRC, B, false, true, true>(src, cur, ctx, o, sm, lane, wave, ws, nc);
                 else
-                    classify_tile<true, false, Source, DT, SRC, B, false, PRE>(src, cur, ctx, o, sm, lane, wave, ws, nc);
+                    classify_tile<true, false, Source, DT, SRC, B, false, true, false>(src, cur, ctx, o, sm, lane, wave, ws, nc);
+            } else if constexpr (SRC != SRC_RUNTIME) {
+                if (floatcmp)
+                    classify_tile<true, true, Source, DT, SRC, B, false, false>(src, cur, ctx, o, sm, lane, wave, ws, nc);
+                else
+                    classify_tile<true, false, Source, DT, SRC, B, false, false>(src, cur, ctx, o, sm, lane, wave, ws, nc);
             } else {
                 classify_tile<true, false, Source, DT, SRC, B>(src, cur, ctx, o, sm, lane, wave, ws, nc);
             }
         },
         [&](const typename Source::Tile& cur) {
-            classify_tile<false, false, Source, DT, SRC, B, false, PRE>(src, cur, ctx, o, sm, lane, wave, ws, nc);
+            classify_tile<false, false, Source, DT, SRC, B, false, PRE, true>(src, cur, ctx, o, sm, lane, wave, ws, nc);
         });
     if (ws.fillW) flush_winners<DT>(o, sm.wbuf[wave], &sm.runW, ws.fillW, lane);
     if (ws.fillC) flush_candidates<DT>(o, sm.cbuf[wave], &sm.runC, ws.fillC, lane, nc);
@@ -867,6 +918,7 @@ __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Par
                 u32* seg = P.seg + (((size_t)((pn - 1) & 1) * P.batch + row) * P.G + wg) * 2;
                 seg[0] = runC;
                 seg[1] = PRE ? sm.runC - runC : myC;  // (the prefilter learns its count by writing)
+                if (PRE) atomicAdd(&st->pre_kept, sm.runC - runC);
             }
         }
     }
@@ -903,8 +955,7 @@ template <int DT>
 __device__ __forceinline__ float init_row(const Params& P, int row, rtopk_row_trace* st) {
     static_assert(sizeof(rtopk_row_trace) / 4 <= 128 && offsetof(rtopk_row_trace, a_s) == 0, "trace layout");
     u32* w = (u32*)st;
-    if (threadIdx.x >= 1 && threadIdx.x < sizeof(rtopk_row_trace) / 4 && threadIdx.x != offsetof(rtopk_row_trace, pre_elems) / 4)
-        w[threadIdx.x] = 0;
+    if (threadIdx.x >= 1 && threadIdx.x < sizeof(rtopk_row_trace) / 4) w[threadIdx.x] = 0;
     float a_s = 0.0f;
     if (threadIdx.x == 0) {
         if (DT == RTOPK_F32 && (P.flags & RTOPK_FLAG_SCALING)) {
@@ -913,9 +964,6 @@ __device__ __forceinline__ float init_row(const Params& P, int row, rtopk_row_tr
             if ((bits & 0x7f800000u) != 0x7f800000u) a_s = __uint_as_float(bits);  // finite only
         }
         st->a_s = a_s;
-        // how much of the row is counted before a prefilter sweep (0: no prefilter)
-        const u64 part = (u64)P.pre_tiles * (u64)(kGridBlock * kHostElemsPerLane);
-        st->pre_elems = part < (u64)P.n ? (u32)part : (P.pre_tiles ? (u32)P.n : 0u);
     }
     return a_s;
 }
@@ -963,23 +1011,37 @@ __global__ void __launch_bounds__(kGridBlock) k_classify_keys(Params P) {
     const u32 ntiles = src.ntiles();
     // every workgroup repeats selectBin on the row's global histogram (cheap, and it spares a grid-wide hand-off)
     const Selection sel = select_pass<kGridBlock>(PlainCounts{global_hist(P, 0, row)}, 1 << P.pass[0].bits, e, sm, st);
+    if (P.pre_stride != 0) {
+        // after a prefilter sweep: this sweep runs only if the k-th key's bin lies below what that one kept
+        if (sel.bin >= st->pre_bound) return;
+        if (blockIdx.x == 0 && threadIdx.x == 0) st->pre_missed = 1u;
+    }
     classify_phase<decltype(src), DT, SRC, kGridBlock, false>(src, P, 0, row, blockIdx.x, gridDim.x, e, st, st->a_s, sm, 1u,
                                                               sel, ntiles < gridDim.x ? ntiles : gridDim.x, false);
 }
 
-// The prefilter sweep: selectBin on the first part's histogram bounds the row's bin from below; one sweep over X
-// moves everything from that bin upwards into the candidate array and counts its first digit.  Pass 0 then
-// runs on those candidates like any later pass: X is read once (plus its first part a second time, from the
-// caches) instead of twice.
+// The prefilter sweep.  selectBin on the sample's histogram, for the sample rank that stands for the row's k-th
+// key (with a margin), gives a bin that very probably is the k-th key's or lies below it.  ONE sweep over X then
+// does pass 0's countBin for every element (so selectBin of pass 0 is exact, as after a HIST sweep) and moves
+// everything from that bin upwards into the candidate array.  Pass 0 runs on those candidates like any later
+// pass: X is read once instead of twice.  When the exact counts put the k-th key's bin below the bound, the
+// ordinary CLASSIFY sweep over X runs instead (k_classify_keys, idle otherwise); the result never depends on
+// the sample.
 template <int DT, int SRC, bool NT>
 __global__ void __launch_bounds__(kGridBlock) k_prefilter_keys(Params P) {
     __shared__ Shared<kGridBlock> sm;
     const int row = blockIdx.y;
     rtopk_row_trace* st = row_state(P, row);
-    const PassEntry e = pass_entry(P, st, 0);
+    PassEntry e = pass_entry(P, st, 0);
     KeySource<DT, kGridBlock, key_vecs<DT>(), NT> src;
     src.init(P.keys, P.n, row);
-    const Selection sel = select_pass<kGridBlock>(PlainCounts{global_hist(P, 2, row)}, 1 << P.pass[0].bits, e, sm, st);
+    const RowSample sample = row_sample(src, P);
+    // a rank beyond the sample (or an empty sample) selects nothing: bin 0, everything is kept
+    e.k_rem = sample.rank < (u64)sample.elems ? (u32)sample.rank : sample.elems + 1u;
+    bool ignored;
+    const Selection sel = select_pass<kGridBlock>(PlainCounts{global_hist(P, 2, row)}, 1 << P.pass[0].bits, e, sm, st, &ignored);
+    if (blockIdx.x == 0 && threadIdx.x == 0) st->pre_bound = sel.bin;
+    e.k_rem = (u32)P.k;
     classify_phase<decltype(src), DT, SRC, kGridBlock, false, NoResident, true>(src, P, 0, row, blockIdx.x, gridDim.x, e, st,
                                                                                 st->a_s, sm, 1u, sel, gridDim.x, false);
 }
@@ -1001,6 +1063,8 @@ __global__ void __launch_bounds__(kGridBlock) k_classify_cand(Params P, int p) {
     src.init(P.cand[(p - 1) & 1] + (size_t)row * P.cand_stride, seg[0], seg[1], (u32)P.cand_stride);
     // its own tiles only: the segment is this workgroup's alone
     const Selection sel = select_pass<kGridBlock>(PlainCounts{global_hist(P, p, row)}, 1 << P.pass[p].bits, e, sm, st);
+    // pass 0 on what a prefilter sweep kept: only if that holds the k-th key's bin (else k_classify_keys has run)
+    if (p == 0 && sel.bin < st->pre_bound) return;
     classify_phase<decltype(src), DT, SRC_RUNTIME, kGridBlock, false>(src, P, p, row, blockIdx.x, gridDim.x, e, st, st->a_s,
                                                                       sm, 1u, sel, gridDim.x, true);
 }
@@ -1567,7 +1631,7 @@ static rtopk_status launch_all(const Params& P, const Config& c, bool scaled, hi
     mark(events, 1, st);
     const bool nt = (P.flags & kInternalStream) != 0;
     if (c.prefilter) {
-        // first part's histogram, then the prefilter sweep (never scaled: make_config)
+        // the sample's histogram, then the prefilter sweep (never scaled: make_config)
         if (nt) {
             hipLaunchKernelGGL((k_hist_keys<DT, SRC_KEY, true>), grid, block, 0, st, P);
             mark(events, 2, st);
@@ -1595,6 +1659,13 @@ static rtopk_status launch_all(const Params& P, const Config& c, bool scaled, hi
         hipLaunchKernelGGL((k_classify_keys<DT, SRC_KEY, false>), grid, block, 0, st, P);
     }
     mark(events, 3, st);
+    if (c.prefilter) {
+        // the second sweep over X, for rows whose sample misled the prefilter (the others leave at once)
+        if (nt)
+            hipLaunchKernelGGL((k_classify_keys<DT, SRC_KEY, true>), grid, block, 0, st, P);
+        else
+            hipLaunchKernelGGL((k_classify_keys<DT, SRC_KEY, false>), grid, block, 0, st, P);
+    }
     for (int p = c.prefilter ? 0 : 1; p <= c.multi_last && p < c.npass; ++p) {
         hipLaunchKernelGGL((k_classify_cand<DT>), grid, block, 0, st, P, p);
     }

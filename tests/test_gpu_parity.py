@@ -226,15 +226,19 @@ def test_one_sweep_kernel_and_its_hand_over():
 
 @pytest.mark.parametrize("G", [0, 3, 7])
 def test_prefilter_sweep(G):
-    # many workgroups per row with the prefilter forced on: histogram of the first part only, one sweep that
-    # keeps the bins from the bound upwards, pass 0 on what was kept
+    # many workgroups per row with the prefilter forced on: histogram of a sample of the row, one sweep that counts
+    # every digit and keeps the bins from the sample's bound upwards, pass 0 on what was kept
     T = dict(path=2, prefilter=1, wgs_per_row=G)
     for n in (1, 65, 8193, 100003, 300001):
         bits = W.normal(n, seed=60 + n % 13).view(np.uint32)
         for k in sorted({1, min(n, 50), max(1, n // 2), n}):
             for largest in (True, False):
                 tr = _run_and_check("prefilter", bits, F32, k, largest, tuning=T)[0]
-                assert tr.pre_elems != 0 and tr.passes[0].cand_before <= n
+                assert tr.pre_elems <= n and tr.pre_kept <= n
+                if not tr.pre_missed:
+                    assert tr.passes[0].cand_before == tr.pre_kept and tr.passes[0].bin >= tr.pre_bound
+                if n == 300001:     # 36 full tiles of 8192 elements: tiles 0 and 32 are the sample
+                    assert tr.pre_elems == 2 * 8192
     sp = W.specials_ramp(30001, seed=61, with_nan=True).view(np.uint32)
     for k in (5, 1000, 20000):
         for largest in (True, False):
@@ -255,6 +259,26 @@ def test_prefilter_sweep(G):
     tr = _run_and_check("prefilter vs scaling", W.uniform_range(60000, 66, 128.6, 128.7).view(np.uint32), F32, 512, True,
                         scaling=True, tuning=T)[0]
     assert tr.pre_elems == 0
+
+
+@pytest.mark.parametrize("tuning", [dict(), dict(wgs_per_row=7, small_threshold=100)])
+def test_prefilter_with_a_misleading_sample(tuning):
+    # The sample is every 32nd full tile (8192 fp32 elements) of the row.  Here exactly those tiles hold values far
+    # better than the rest and k exceeds their number, so the bin taken from the sample lies above the k-th key's:
+    # the exact counts of the sweep show it, the second sweep over X runs, and the selection is still the oracle's.
+    n, k = 300001, 50000
+    for largest in (True, False):
+        y = W.normal(n, 6).copy()
+        for t in range(0, n // 8192, 32):
+            y[t * 8192:(t + 1) * 8192] = 100.0 if largest else -100.0
+        tr = _run_and_check("misleading sample", y.view(np.uint32), F32, k, largest,
+                            tuning=dict(path=2, prefilter=1, **tuning))[0]
+        assert tr.pre_missed == 1 and tr.pre_kept == tr.pre_elems == 2 * 8192
+        assert tr.passes[0].bin < tr.pre_bound and tr.passes[0].cand_before == n
+    # ... and when k stays within the planted values the same bound is right
+    tr = _run_and_check("planted values suffice", y.view(np.uint32), F32, 10000, False,
+                        tuning=dict(path=2, prefilter=1, **tuning))[0]
+    assert tr.pre_missed == 0 and tr.passes[0].cand_before == tr.pre_kept
 
 
 def test_batch_many_rows_grid_path():
