@@ -21,6 +21,10 @@
 //   A row that one workgroup handles alone keeps all of this in LDS and registers (k_row, k_row_resident,
 //   k_finish); once at most 512 candidates are left they are ranked against each other directly.
 //
+//   Where it pays, the two sweeps over the input become one: a bin to filter by is taken from a part of the
+//   row first (k_row_stream: the row's first part, a guaranteed bound; k_prefilter_keys: a sample, checked
+//   against the exact counts afterwards, with the second sweep as the fallback).
+//
 // Passes walk the digits of the key from the most significant one down and then the digits of
 // (idx_max - index), which makes every element's extended key unique: the loop ends when the chosen
 // bin holds exactly as many candidates as are still wanted (all of them win), at the latest on the last
@@ -734,10 +738,11 @@ enum { HIST_IN_LDS = 0, HIST_IN_GLOBAL = 1 };
 // the running write positions).  SINGLE: the row is handled by this workgroup alone (wg = 0, G = 1);
 // otherwise G workgroups share the row.
 // Returns the loop state for pass p + 1 (what the pass record written here says, without the trip through memory).
-// PRE: the prefilter sweep over X (many workgroups, first digit): `sel` comes from the histogram of the row's first
-// part only, so its bin is a lower bound of the true one; nothing is written to the output, every element of a
-// bin >= sel.bin goes to the candidate array (into a segment of fixed position: there are no counts to derive
-// exact offsets from), and the digit counted for the next pass is this same first digit.
+// PRE: the prefilter sweep over X (many workgroups, first digit): `sel` comes from the histogram of a sample of
+// the row, so its bin is only probably at or below the true one; nothing is written to the output, every element
+// of a bin >= sel.bin goes to the candidate array (into a segment of fixed position: there are no counts yet to
+// derive exact offsets from), and this same first digit is counted for EVERY element of X, kept or not (the
+// exact histogram pass 0 selects on, and the per-workgroup records either kind of pass 0 takes its offsets from).
 template <class Source, int DT, int SRC, int B, bool SINGLE, class Resident = NoResident, bool PRE = false>
 __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Params& P, int p, int row, u32 wg, u32 G,
                                                     const PassEntry& e, rtopk_row_trace* st, float a_s, Shared<B>& sm,
