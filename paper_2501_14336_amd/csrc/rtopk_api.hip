@@ -72,7 +72,11 @@ static rtopk_status make_config(int64_t batch, int64_t n, int64_t k, rtopk_dtype
     }
     if (path == 2) {
         if (G == 0) {
-            int64_t want = 512 / batch;  // about two workgroups per compute unit in total
+            // about two workgroups per compute unit in total; one when the sweep over X also counts and keeps
+            // little (measured on n = 2^28: k = 2^20 276 us with 256 workgroups, 305 with 512, 340 with 192 or
+            // 320; k = 2^22, where at least 1.6 % is kept, 426 against 377; two sweeps with k = 2^24: 641
+            // against 515)
+            int64_t want = (c->prefilter && k <= n / 256 ? 256 : 512) / batch;
             if (want < 1) want = 1;
             G = (int)want;
         }
