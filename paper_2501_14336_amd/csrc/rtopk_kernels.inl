@@ -799,7 +799,7 @@ __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Par
     if (!PRE && wg == 0 && tid == 0) {
         write_pass_record(st, p, ctx.pi, e, sel, where);
         // after a prefilter the first digit pass looks at what the prefilter kept, not at all of X
-        if (!SINGLE && SRC == SRC_RUNTIME && p == 0) st->pass_rec[0].cand_before = st->pre_kept;
+        if (!SINGLE && SRC == SRC_RUNTIME && p == 0) st->pass_rec[0].cand_before = st->pre_kept;  // after a prefilter
     }
 
     // few candidates left and the row is this workgroup's alone: keep them in LDS for the ranking step
@@ -1016,11 +1016,6 @@ __global__ void __launch_bounds__(kGridBlock) k_classify_keys(Params P) {
     const u32 ntiles = src.ntiles();
     // every workgroup repeats selectBin on the row's global histogram (cheap, and it spares a grid-wide hand-off)
     const Selection sel = select_pass<kGridBlock>(PlainCounts{global_hist(P, 0, row)}, 1 << P.pass[0].bits, e, sm, st);
-    if (P.pre_stride != 0) {
-        // after a prefilter sweep: this sweep runs only if the k-th key's bin lies below what that one kept
-        if (sel.bin >= st->pre_bound) return;
-        if (blockIdx.x == 0 && threadIdx.x == 0) st->pre_missed = 1u;
-    }
     classify_phase<decltype(src), DT, SRC, kGridBlock, false>(src, P, 0, row, blockIdx.x, gridDim.x, e, st, st->a_s, sm, 1u,
                                                               sel, ntiles < gridDim.x ? ntiles : gridDim.x, false);
 }
@@ -1029,8 +1024,8 @@ __global__ void __launch_bounds__(kGridBlock) k_classify_keys(Params P) {
 // key (with a margin), gives a bin that very probably is the k-th key's or lies below it.  ONE sweep over X then
 // does pass 0's countBin for every element (so selectBin of pass 0 is exact, as after a HIST sweep) and moves
 // everything from that bin upwards into the candidate array.  Pass 0 runs on those candidates like any later
-// pass: X is read once instead of twice.  When the exact counts put the k-th key's bin below the bound, the
-// ordinary CLASSIFY sweep over X runs instead (k_classify_keys, idle otherwise); the result never depends on
+// pass: X is read once instead of twice.  When the exact counts put the k-th key's bin below the bound, pass 0
+// is the ordinary CLASSIFY sweep over X instead (k_pass0_after_prefilter decides); the result never depends on
 // the sample.
 template <int DT, int SRC, bool NT>
 __global__ void __launch_bounds__(kGridBlock) k_prefilter_keys(Params P) {
@@ -1051,16 +1046,39 @@ __global__ void __launch_bounds__(kGridBlock) k_prefilter_keys(Params P) {
                                                                                 st->a_s, sm, 1u, sel, gridDim.x, false);
 }
 
-// Pass p on the grid (p >= 1, or p = 0 after a prefilter): workgroup w classifies the candidates workgroup w kept
-// in the sweep before.
+// Pass 0 after a prefilter sweep.  Every workgroup repeats selectBin on the exact counts that sweep left.  If the
+// k-th key's bin is among those the sweep kept (nearly always), workgroup w classifies the candidates workgroup w
+// kept, as in any later pass; otherwise the sample misled the prefilter and this is the ordinary CLASSIFY sweep
+// over X (same tiles per workgroup as in the prefilter sweep, whose per-workgroup records give the offsets).
+template <int DT, bool NT>
+__global__ void __launch_bounds__(kGridBlock) k_pass0_after_prefilter(Params P) {
+    __shared__ Shared<kGridBlock> sm;
+    const int row = blockIdx.y;
+    rtopk_row_trace* st = row_state(P, row);
+    const PassEntry e = pass_entry(P, st, 0);
+    const Selection sel = select_pass<kGridBlock>(PlainCounts{global_hist(P, 0, row)}, 1 << P.pass[0].bits, e, sm, st);
+    if (sel.bin >= st->pre_bound) {
+        const u32* seg = P.seg + (((size_t)1 * P.batch + row) * P.G + blockIdx.x) * 2;
+        CandSource<kGridBlock, kVecs> src;
+        src.init(P.cand[1] + (size_t)row * P.cand_stride, seg[0], seg[1], (u32)P.cand_stride);
+        classify_phase<decltype(src), DT, SRC_RUNTIME, kGridBlock, false>(src, P, 0, row, blockIdx.x, gridDim.x, e, st,
+                                                                          st->a_s, sm, 1u, sel, gridDim.x, true);
+    } else {
+        if (blockIdx.x == 0 && threadIdx.x == 0) st->pre_missed = 1u;
+        KeySource<DT, kGridBlock, key_vecs<DT>(), NT> src;
+        src.init(P.keys, P.n, row);
+        const u32 ntiles = src.ntiles();
+        classify_phase<decltype(src), DT, SRC_KEY, kGridBlock, false>(src, P, 0, row, blockIdx.x, gridDim.x, e, st, st->a_s,
+                                                                      sm, 1u, sel, ntiles < gridDim.x ? ntiles : gridDim.x, false);
+    }
+}
+
+// Pass p >= 1 on the grid: workgroup w classifies the candidates workgroup w kept in the sweep before.
 template <int DT>
 __global__ void __launch_bounds__(kGridBlock) k_classify_cand(Params P, int p) {
     __shared__ Shared<kGridBlock> sm;
     const int row = blockIdx.y;
     rtopk_row_trace* st = row_state(P, row);
-#ifdef RTOPK_TIMING
-    if (p == 0 && threadIdx.x == 0) P.dbg[((size_t)row * P.G + blockIdx.x) * 16 + 5] = wall_clock64();
-#endif
     const PassEntry e = pass_entry(P, st, p);
     if (!multi_runs_pass(P, e, p)) return;
     const u32* seg = P.seg + (((size_t)((p - 1) & 1) * P.batch + row) * P.G + blockIdx.x) * 2;
@@ -1068,8 +1086,6 @@ __global__ void __launch_bounds__(kGridBlock) k_classify_cand(Params P, int p) {
     src.init(P.cand[(p - 1) & 1] + (size_t)row * P.cand_stride, seg[0], seg[1], (u32)P.cand_stride);
     // its own tiles only: the segment is this workgroup's alone
     const Selection sel = select_pass<kGridBlock>(PlainCounts{global_hist(P, p, row)}, 1 << P.pass[p].bits, e, sm, st);
-    // pass 0 on what a prefilter sweep kept: only if that holds the k-th key's bin (else k_classify_keys has run)
-    if (p == 0 && sel.bin < st->pre_bound) return;
     classify_phase<decltype(src), DT, SRC_RUNTIME, kGridBlock, false>(src, P, p, row, blockIdx.x, gridDim.x, e, st, st->a_s,
                                                                       sm, 1u, sel, gridDim.x, true);
 }
@@ -1665,13 +1681,13 @@ static rtopk_status launch_all(const Params& P, const Config& c, bool scaled, hi
     }
     mark(events, 3, st);
     if (c.prefilter) {
-        // the second sweep over X, for rows whose sample misled the prefilter (the others leave at once)
+        // pass 0: on what the prefilter kept, or over X again for rows whose sample misled it
         if (nt)
-            hipLaunchKernelGGL((k_classify_keys<DT, SRC_KEY, true>), grid, block, 0, st, P);
+            hipLaunchKernelGGL((k_pass0_after_prefilter<DT, true>), grid, block, 0, st, P);
         else
-            hipLaunchKernelGGL((k_classify_keys<DT, SRC_KEY, false>), grid, block, 0, st, P);
+            hipLaunchKernelGGL((k_pass0_after_prefilter<DT, false>), grid, block, 0, st, P);
     }
-    for (int p = c.prefilter ? 0 : 1; p <= c.multi_last && p < c.npass; ++p) {
+    for (int p = 1; p <= c.multi_last && p < c.npass; ++p) {
         hipLaunchKernelGGL((k_classify_cand<DT>), grid, block, 0, st, P, p);
     }
     hipLaunchKernelGGL((k_finish<DT>), dim3(batch), dim3(kRowBlock), 0, st, P);
