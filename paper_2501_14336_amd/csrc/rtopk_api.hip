@@ -55,10 +55,11 @@ static rtopk_status make_config(int64_t batch, int64_t n, int64_t k, rtopk_dtype
     const int eb = elem_bytes(dt);
     const int64_t tile_elems = (int64_t)kHostGridBlock * kHostElemsPerLane;  // 16 elements per lane for every type
     const int64_t ntiles = (n + 16 / eb - 1 + tile_elems) / tile_elems;  // one spare for the lead-in
-    // Prefilter (many workgroups per row, unscaled): count a sample of the row (every 32nd tile), take from it a
-    // bin that very probably lies at or below the k-th key's, and sweep X ONCE, counting every element's digit
-    // and keeping the elements from that bin upwards; pass 0 then runs on what was kept.  If the full counts
-    // show the bin was too high, the ordinary second sweep over X runs instead (one idle launch otherwise).
+    // Prefilter (many workgroups per row, unscaled): count a sample of the row (every 31st tile: a prime stride,
+    // so that no power-of-two period in the data lines up with the sample), take from it a bin that very
+    // probably lies at or below the k-th key's, and sweep X ONCE, counting every element's digit and keeping the
+    // elements from that bin upwards; pass 0 then runs on what was kept.  If the full counts show the bin was
+    // too high, pass 0 is the ordinary second sweep over X instead.
     // It pays while k is well below n (what is kept is written out and read again).
     c->prefilter = false;
     c->pre_stride = 0;
@@ -68,7 +69,7 @@ static rtopk_status make_config(int64_t batch, int64_t n, int64_t k, rtopk_dtype
     if (path == 2 && !scaling_on &&
         (pre_knob == 1 || (pre_knob == 0 && batch * n * eb >= ((int64_t)256 << 20) && k <= n / 32))) {
         c->prefilter = true;
-        c->pre_stride = 32;
+        c->pre_stride = 31;
     }
     if (path == 2) {
         if (G == 0) {

@@ -237,7 +237,7 @@ def test_prefilter_sweep(G):
                 assert tr.pre_elems <= n and tr.pre_kept <= n
                 if not tr.pre_missed:
                     assert tr.passes[0].cand_before == tr.pre_kept and tr.passes[0].bin >= tr.pre_bound
-                if n == 300001:     # 36 full tiles of 8192 elements: tiles 0 and 32 are the sample
+                if n == 300001:     # 36 full tiles of 8192 elements: tiles 0 and 31 are the sample
                     assert tr.pre_elems == 2 * 8192
     sp = W.specials_ramp(30001, seed=61, with_nan=True).view(np.uint32)
     for k in (5, 1000, 20000):
@@ -263,13 +263,13 @@ def test_prefilter_sweep(G):
 
 @pytest.mark.parametrize("tuning", [dict(), dict(wgs_per_row=7, small_threshold=100)])
 def test_prefilter_with_a_misleading_sample(tuning):
-    # The sample is every 32nd full tile (8192 fp32 elements) of the row.  Here exactly those tiles hold values far
+    # The sample is every 31st full tile (8192 fp32 elements) of the row.  Here exactly those tiles hold values far
     # better than the rest and k exceeds their number, so the bin taken from the sample lies above the k-th key's:
     # the exact counts of the sweep show it, the second sweep over X runs, and the selection is still the oracle's.
     n, k = 300001, 50000
     for largest in (True, False):
         y = W.normal(n, 6).copy()
-        for t in range(0, n // 8192, 32):
+        for t in range(0, n // 8192, 31):
             y[t * 8192:(t + 1) * 8192] = 100.0 if largest else -100.0
         tr = _run_and_check("misleading sample", y.view(np.uint32), F32, k, largest,
                             tuning=dict(path=2, prefilter=1, **tuning))[0]
