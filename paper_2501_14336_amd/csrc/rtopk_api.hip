@@ -77,7 +77,9 @@ static rtopk_status make_config(int64_t batch, int64_t n, int64_t k, rtopk_dtype
             // little (measured on n = 2^28: k = 2^20 276 us with 256 workgroups, 305 with 512, 340 with 192 or
             // 320; k = 2^22, where at least 1.6 % is kept, 426 against 377; two sweeps with k = 2^24: 641
             // against 515)
-            int64_t want = (c->prefilter && k <= n / 256 ? 256 : 512) / batch;
+            // (16-bit keys: whole bins of an 11-bit digit are kept, more of the row; 2^29 fp16 keys, k = 2^20:
+            // 260 us with 512, 346 with 256; bf16 with k = 50 or 2^10: no difference)
+            int64_t want = (c->prefilter && dt == RTOPK_F32 && k <= n / 256 ? 256 : 512) / batch;
             if (want < 1) want = 1;
             G = (int)want;
         }
