@@ -281,6 +281,22 @@ def test_prefilter_with_a_misleading_sample(tuning):
     assert tr.pre_missed == 0 and tr.passes[0].cand_before == tr.pre_kept
 
 
+def test_prefilter_sample_holds_on_independent_draws():
+    # On rows of independent draws the bin taken from the sample (with its margin) never lies above the k-th key's
+    # bin: the second sweep stays unused, whatever k, and what is kept stays a small part of the row.
+    T = dict(path=2, prefilter=1)
+    for n, seed in ((1 << 20, 71), (3000001, 72), (1 << 22, 73)):
+        for gen in (lambda: W.normal(n, seed), lambda: W.uniform_range(n, seed, -1e6, 1e6), lambda: W.zipf(n, seed).astype(np.float32)):
+            bits = gen().view(np.uint32)
+            for k in (1, 37, 1000, n // 1000, n // 100, n // 32):
+                tr = _run_and_check("independent draws", bits, F32, k, True, tuning=T)[0]
+                assert tr.pre_missed == 0 and tr.pre_bound <= tr.passes[0].bin
+    bits = W.llm_logits(4, 1 << 20, 74)
+    x = to_device(bits, BF16)
+    _, _, trs, _ = gpu_topk(x, BF16, 50, True, tuning=T)
+    assert all(t.pre_missed == 0 for t in trs)
+
+
 def test_batch_many_rows_grid_path():
     bits = W.normal(64 * 20000, 15).view(np.uint32).reshape(64, 20000)
     _run_and_check("batch 64 grid", bits, F32, 333, True, tuning=dict(path=2, small_threshold=16))
