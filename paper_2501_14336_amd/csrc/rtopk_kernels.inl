@@ -1039,7 +1039,11 @@ __global__ void __launch_bounds__(kGridBlock) k_prefilter_keys(Params P) {
     // a rank beyond the sample (or an empty sample) selects nothing: bin 0, everything is kept
     e.k_rem = sample.rank < (u64)sample.elems ? (u32)sample.rank : sample.elems + 1u;
     bool ignored;
-    const Selection sel = select_pass<kGridBlock>(PlainCounts{global_hist(P, 2, row)}, 1 << P.pass[0].bits, e, sm, st, &ignored);
+    Selection sel = select_pass<kGridBlock>(PlainCounts{global_hist(P, 2, row)}, 1 << P.pass[0].bits, e, sm, st, &ignored);
+    // If the sample says that more than a sixteenth of the row lies in the bins that would be kept (keys crowded
+    // into one bin: a narrow range, many duplicates), writing that much out and reading it back costs more than
+    // the second sweep over X: keep nothing (a bound above every bin), only count, and let pass 0 sweep X.
+    if ((u64)(sel.above + sel.inside) * 16u > (u64)sample.elems) sel.bin = 1u << P.pass[0].bits;
     if (blockIdx.x == 0 && threadIdx.x == 0) st->pre_bound = sel.bin;
     e.k_rem = (u32)P.k;
     classify_phase<decltype(src), DT, SRC, kGridBlock, false, NoResident, true>(src, P, 0, row, blockIdx.x, gridDim.x, e, st,
@@ -1064,7 +1068,7 @@ __global__ void __launch_bounds__(kGridBlock) k_pass0_after_prefilter(Params P) 
         classify_phase<decltype(src), DT, SRC_RUNTIME, kGridBlock, false>(src, P, 0, row, blockIdx.x, gridDim.x, e, st,
                                                                           st->a_s, sm, 1u, sel, gridDim.x, true);
     } else {
-        if (blockIdx.x == 0 && threadIdx.x == 0) st->pre_missed = 1u;
+        if (blockIdx.x == 0 && threadIdx.x == 0) st->pre_missed = st->pre_bound == (1u << P.pass[0].bits) ? 2u : 1u;
         KeySource<DT, kGridBlock, key_vecs<DT>(), NT> src;
         src.init(P.keys, P.n, row);
         const u32 ntiles = src.ntiles();

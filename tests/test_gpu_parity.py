@@ -264,21 +264,33 @@ def test_prefilter_sweep(G):
 @pytest.mark.parametrize("tuning", [dict(), dict(wgs_per_row=7, small_threshold=100)])
 def test_prefilter_with_a_misleading_sample(tuning):
     # The sample is every 31st full tile (8192 fp32 elements) of the row.  Here exactly those tiles hold values far
-    # better than the rest and k exceeds their number, so the bin taken from the sample lies above the k-th key's:
-    # the exact counts of the sweep show it, the second sweep over X runs, and the selection is still the oracle's.
-    n, k = 300001, 50000
+    # better than the rest (spread over many bins, so that the sample does not look crowded), and k exceeds their
+    # number, so the bin taken from the sample lies above the k-th key's: the exact counts of the sweep show it, the
+    # second sweep over X runs, and the selection is still the oracle's.
+    n, k = 2000003, 70000
+    planted = (10.0 ** (2.0 + 6.0 * W.uniform01(n, 77))).astype(np.float32)
     for largest in (True, False):
         y = W.normal(n, 6).copy()
         for t in range(0, n // 8192, 31):
-            y[t * 8192:(t + 1) * 8192] = 100.0 if largest else -100.0
+            y[t * 8192:(t + 1) * 8192] = planted[t * 8192:(t + 1) * 8192] * (1.0 if largest else -1.0)
         tr = _run_and_check("misleading sample", y.view(np.uint32), F32, k, largest,
                             tuning=dict(path=2, prefilter=1, **tuning))[0]
-        assert tr.pre_missed == 1 and tr.pre_kept == tr.pre_elems == 2 * 8192
+        assert tr.pre_missed == 1 and tr.pre_elems == 8 * 8192 and 0 < tr.pre_kept < tr.pre_elems
         assert tr.passes[0].bin < tr.pre_bound and tr.passes[0].cand_before == n
-    # ... and when k stays within the planted values the same bound is right
-    tr = _run_and_check("planted values suffice", y.view(np.uint32), F32, 10000, False,
-                        tuning=dict(path=2, prefilter=1, **tuning))[0]
-    assert tr.pre_missed == 0 and tr.passes[0].cand_before == tr.pre_kept
+
+
+def test_prefilter_declines_when_the_keys_crowd_into_the_bins_to_keep():
+    # a narrow range, or mostly one value: the sample shows that nearly the whole row would be kept, so the sweep
+    # keeps nothing (it only counts) and pass 0 is the ordinary sweep over X
+    T = dict(path=2, prefilter=1)
+    # (duplicates: nine in ten keys are 0.999, the rest uniform in [0, 1) -- crowded only from the top)
+    for name, bits, directions in (("narrow", W.narrow(300001, 75).view(np.uint32), (True, False)),
+                                   ("duplicates", W.duplicates(300001, 76).view(np.uint32), (True,))):
+        for k in (100, 20000):
+            for largest in directions:
+                tr = _run_and_check("declined " + name, bits, F32, k, largest, tuning=T)[0]
+                assert tr.pre_missed == 2 and tr.pre_kept == 0 and tr.pre_bound == 4096
+                assert tr.passes[0].cand_before == 300001
 
 
 def test_prefilter_sample_holds_on_independent_draws():
@@ -288,7 +300,7 @@ def test_prefilter_sample_holds_on_independent_draws():
     for n, seed in ((1 << 20, 71), (3000001, 72), (1 << 22, 73)):
         for gen in (lambda: W.normal(n, seed), lambda: W.uniform_range(n, seed, -1e6, 1e6), lambda: W.zipf(n, seed).astype(np.float32)):
             bits = gen().view(np.uint32)
-            for k in (1, 37, 1000, n // 1000, n // 100, n // 32):
+            for k in (1, 37, 1000, n // 1000, n // 100, n // 64):
                 tr = _run_and_check("independent draws", bits, F32, k, True, tuning=T)[0]
                 assert tr.pre_missed == 0 and tr.pre_bound <= tr.passes[0].bin
     bits = W.llm_logits(4, 1 << 20, 74)
