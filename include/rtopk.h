@@ -156,7 +156,7 @@ typedef struct {
     uint32_t pre_missed;       /* 1: the k-th key's bin lies below pre_bound (the sample misled), so
                                   pass 0 swept the row again instead of reading what was kept;
                                   2: the same on purpose -- the sample showed the keys crowded into the
-                                  bins to keep (over 1/16 of the row), so the sweep kept nothing
+                                  bins to keep (over 1/8 of the row; 1/16 for 16-bit keys), so the sweep kept nothing
                                   (pre_bound is the bin count) and only counted                     */
     uint32_t reserved[8];
     struct {

@@ -1040,10 +1040,12 @@ __global__ void __launch_bounds__(kGridBlock) k_prefilter_keys(Params P) {
     e.k_rem = sample.rank < (u64)sample.elems ? (u32)sample.rank : sample.elems + 1u;
     bool ignored;
     Selection sel = select_pass<kGridBlock>(PlainCounts{global_hist(P, 2, row)}, 1 << P.pass[0].bits, e, sm, st, &ignored);
-    // If the sample says that more than a sixteenth of the row lies in the bins that would be kept (keys crowded
-    // into one bin: a narrow range, many duplicates), writing that much out and reading it back costs more than
-    // the second sweep over X: keep nothing (a bound above every bin), only count, and let pass 0 sweep X.
-    if ((u64)(sel.above + sel.inside) * 16u > (u64)sample.elems) sel.bin = 1u << P.pass[0].bits;
+    // If the sample says that more than an eighth of the row (a sixteenth for 16-bit keys, whose candidates are
+    // four times their size) lies in the bins that would be kept -- keys crowded into one bin: a narrow range,
+    // many duplicates --, writing that much out and reading it back costs more than the second sweep over X:
+    // keep nothing (a bound above every bin), only count, and let pass 0 sweep X.
+    constexpr u32 kCrowded = DT == RTOPK_F32 ? 8u : 16u;
+    if ((u64)(sel.above + sel.inside) * kCrowded > (u64)sample.elems) sel.bin = 1u << P.pass[0].bits;
     if (blockIdx.x == 0 && threadIdx.x == 0) st->pre_bound = sel.bin;
     e.k_rem = (u32)P.k;
     classify_phase<decltype(src), DT, SRC, kGridBlock, false, NoResident, true>(src, P, 0, row, blockIdx.x, gridDim.x, e, st,
