@@ -60,7 +60,8 @@ enum {
  * code path on the same input.  A field left 0 means "library default".
  */
 typedef struct {
-    int32_t digit_bits;      /* radix digit width d, 8..12 (default 12 for fp32, 11 for 16-bit keys)           */
+    int32_t digit_bits;      /* radix digit width d, 8..12 (default 12; 11 for 16-bit keys when one workgroup
+                                handles a row)                                                                  */
     int32_t path;            /* 0 auto, 1 one workgroup per row (fused kernel), 2 many workgroups per row,
                                 3 like 1, with the one-sweep kernel for small k first (auto picks it for
                                 large batches of rows with k <= 256)                                            */

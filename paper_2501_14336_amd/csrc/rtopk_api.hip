@@ -52,6 +52,10 @@ static rtopk_status make_config(int64_t batch, int64_t n, int64_t k, rtopk_dtype
     if (path == 3) path = 1;
     else if (path == 1 && (!tn || tn->path == 0) && k <= 256 && n >= 16384 && (batch >= 16 || n >= 131072)) one_sweep = true;
     if (path == 2 && batch > 65535) return RTOPK_ERR_INVALID_ARG;  // rows are the grid's y dimension
+    // 16-bit keys on long rows: a 12-bit first digit (4 bits left for the second) instead of 11 + 5 -- the first
+    // sweep then keeps a bin of half the width (bf16 logits, 64 x 2^22, k = 50: 200 -> 167 us; 2^29 uniform bf16
+    // keys: 1052 -> 788 us); the one-workgroup-per-row kernels stay at 11, where twice the histogram copies fit
+    if (path == 2 && dt != RTOPK_F32 && !(tn && tn->digit_bits)) d = 12;
     const int eb = elem_bytes(dt);
     const int64_t tile_elems = (int64_t)kHostGridBlock * kHostElemsPerLane;  // 16 elements per lane for every type
     const int64_t ntiles = (n + 16 / eb - 1 + tile_elems) / tile_elems;  // one spare for the lead-in
