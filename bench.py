@@ -105,6 +105,12 @@ def main() -> int:
     # ---- algorithmic bytes from the run's own pass records
     tr = B.read_trace(ws, 1)[0]
     assert tr.error == 0 and tr.done, "device reported an inconsistent state"
+
+    # ---- parity of the LAST TIMED step's output: the definition check (O(n), independent of the method) decides
+    # whether it is the top-k of the row
+    from tests import verify
+    verify.check_topk_properties(x_host.view(np.uint32), verify.F32, k, True,
+                                 vals[0].view(torch.int32).cpu().numpy().view(np.uint32), idx[0].cpu().numpy())
     p0 = tr.passes[0]
     es = 4
     prefilter = tr.pre_elems != 0
@@ -152,6 +158,7 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
+        "parity_checked": True,
         "config": {"workload": "config4: 1 x 2^%d fp32 U[-1e6,1e6) seed 4000, k=2^%d, largest, int64 indices"
                                % (args.log2n, args.log2k),
                    "batch": 1, "n": n, "k": k},

@@ -48,7 +48,10 @@ enum {
      * the exponents of keys clustered near a_s.  The rounded difference orders keys weakly, so
      * the library finishes the selection on the unscaled key; the result is identical with and
      * without the flag and for every seed.  Ignored for 16-bit keys. */
-    RTOPK_FLAG_SCALING = 1u << 0
+    RTOPK_FLAG_SCALING = 1u << 0,
+    /* Accepted and without effect: the per-pass records (rtopk_row_trace below) are the library's own
+     * loop state, so they are written on every call. */
+    RTOPK_FLAG_DEBUG_COUNTERS = 1u << 1
 };
 
 /* Maximum row length: indices are kept in 32 bits inside the library. */
@@ -77,10 +80,18 @@ typedef struct {
  * Size in bytes of the device scratch buffer rtopk_select needs for these arguments
  * (two candidate arrays of n (value, index) pairs per row, per-workgroup histograms, per-row
  * state -- the "workspace in global memory" of paper Section 2.2.3).  Host-only, launches nothing.
- * `tuning` may be NULL.  Returns RTOPK_ERR_INVALID_ARG on bad arguments and leaves *bytes_out.
+ * Returns RTOPK_ERR_INVALID_ARG on bad arguments and leaves *bytes_out.
+ *
+ * The two sizing calls pair with the two selection calls: rtopk_workspace_bytes with rtopk_select
+ * (library defaults), rtopk_workspace_bytes_ex with rtopk_select_ex / rtopk_select_events and the SAME
+ * tuning (NULL = defaults, the same size as rtopk_workspace_bytes).  A tuning that forces many workgroups
+ * per row on a shape whose default is one workgroup per row needs the larger buffer; a buffer sized
+ * without it is rejected with RTOPK_ERR_WORKSPACE_TOO_SMALL before anything is launched.
  */
 rtopk_status rtopk_workspace_bytes(int64_t batch, int64_t n, int64_t k, rtopk_dtype dt, uint32_t flags,
-                                   const rtopk_tuning* tuning, size_t* bytes_out);
+                                   size_t* bytes_out);
+rtopk_status rtopk_workspace_bytes_ex(int64_t batch, int64_t n, int64_t k, rtopk_dtype dt, uint32_t flags,
+                                      const rtopk_tuning* tuning, size_t* bytes_out);
 
 /*
  * Enqueue the selection on `hip_stream` (a hipStream_t; NULL = the default stream) and return
@@ -99,10 +110,17 @@ rtopk_status rtopk_workspace_bytes(int64_t batch, int64_t n, int64_t k, rtopk_dt
  *                selected elements' original bits (NaN payloads and zero signs preserved).
  *   out_indices  device, [batch][k] int64, 8-byte aligned; position of each selected element in its row.
  *   workspace    device, 256-byte aligned, at least rtopk_workspace_bytes(...) bytes computed with the
- *                same batch, n, k, dt, flags and tuning.  Contents are undefined afterwards.  Two calls
- *                that may overlap in time must not share a workspace.
+ *                same batch, n, k, dt and flags (rtopk_workspace_bytes_ex with the same tuning for the
+ *                calls that take one).  Contents are undefined afterwards.  Two calls that may overlap in
+ *                time must not share a workspace.
  *
- * Errors are detected on the host before anything is launched; on error no output is written.
+ * The returned status covers the arguments and the launches only: argument errors are detected on the
+ * host before anything is launched (no output is written then), and RTOPK_ERR_HIP reports a launch the
+ * runtime rejected during THIS call (an error left behind by earlier HIP calls of the process is cleared
+ * first, not reported).  The kernels run after the call returns; if one of them meets a state that cannot
+ * occur in a consistent run (counts that do not add up), it sets a bit in rtopk_row_trace.error of that
+ * row, drops the writes that would leave the buffers, and the row's output is then incomplete.  A caller
+ * that wants this checked reads the row records after the stream has drained (see rtopk_row_trace).
  */
 rtopk_status rtopk_select(const void* keys, int64_t batch, int64_t n, int64_t k, rtopk_dtype dt, int largest,
                           uint32_t flags, uint64_t seed, void* out_values, int64_t* out_indices,

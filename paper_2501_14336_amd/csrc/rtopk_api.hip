@@ -25,7 +25,7 @@ static rtopk_status make_config(int64_t batch, int64_t n, int64_t k, rtopk_dtype
                                 const rtopk_tuning* tn, Config* c) {
     if (batch < 1 || batch > 0x7fffffff || n < 1 || n > RTOPK_MAX_N || k < 1 || k > n) return RTOPK_ERR_INVALID_ARG;
     if (dt != RTOPK_F32 && dt != RTOPK_F16 && dt != RTOPK_BF16) return RTOPK_ERR_INVALID_ARG;
-    if (flags & ~(uint32_t)RTOPK_FLAG_SCALING) return RTOPK_ERR_INVALID_ARG;
+    if (flags & ~(uint32_t)(RTOPK_FLAG_SCALING | RTOPK_FLAG_DEBUG_COUNTERS)) return RTOPK_ERR_INVALID_ARG;
     int d = dt == RTOPK_F32 ? 12 : 11;
     int path = 0, G = 0;
     u32 small = 65536;
@@ -181,7 +181,8 @@ const char* rtopk_status_string(rtopk_status s) {
     switch (s) {
         case RTOPK_OK: return "ok";
         case RTOPK_ERR_INVALID_ARG: return "invalid argument";
-        case RTOPK_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+        case RTOPK_ERR_WORKSPACE_TOO_SMALL:
+            return "workspace too small for these arguments and tuning (size it with rtopk_workspace_bytes_ex and the same tuning)";
         case RTOPK_ERR_UNSUPPORTED: return "unsupported (misaligned buffer)";
         case RTOPK_ERR_HIP: return "HIP runtime rejected a launch";
     }
@@ -190,14 +191,19 @@ const char* rtopk_status_string(rtopk_status s) {
 
 const char* rtopk_version(void) { return "0.1"; }
 
-rtopk_status rtopk_workspace_bytes(int64_t batch, int64_t n, int64_t k, rtopk_dtype dt, uint32_t flags,
-                                   const rtopk_tuning* tuning, size_t* bytes_out) {
+rtopk_status rtopk_workspace_bytes_ex(int64_t batch, int64_t n, int64_t k, rtopk_dtype dt, uint32_t flags,
+                                      const rtopk_tuning* tuning, size_t* bytes_out) {
     if (!bytes_out) return RTOPK_ERR_INVALID_ARG;
     Config c;
     rtopk_status s = make_config(batch, n, k, dt, 1, flags, tuning, &c);
     if (s != RTOPK_OK) return s;
     *bytes_out = make_layout(batch, n, c).total;
     return RTOPK_OK;
+}
+
+rtopk_status rtopk_workspace_bytes(int64_t batch, int64_t n, int64_t k, rtopk_dtype dt, uint32_t flags,
+                                   size_t* bytes_out) {
+    return rtopk_workspace_bytes_ex(batch, n, k, dt, flags, nullptr, bytes_out);
 }
 
 rtopk_status rtopk_select_events(const void* keys, int64_t batch, int64_t n, int64_t k, rtopk_dtype dt, int largest,
@@ -256,6 +262,7 @@ rtopk_status rtopk_select_events(const void* keys, int64_t batch, int64_t n, int
     for (int i = 0; i < c.npass; ++i) P.pass[i] = c.pass[i];
 
     hipStream_t st = (hipStream_t)hip_stream;
+    (void)hipGetLastError();  // an error left by earlier HIP calls of the process is not this call's
     const bool scaled = (flags & RTOPK_FLAG_SCALING) && dt == RTOPK_F32;
     switch (dt) {
         case RTOPK_F32: return launch_f32(P, c, scaled, st, events);

@@ -60,7 +60,7 @@ def test_workspace_bytes_scales_with_the_candidate_arrays():
 
 
 @pytest.mark.parametrize("args", [
-    dict(batch=0), dict(n=0), dict(k=0), dict(k=11), dict(dtype=3), dict(dtype=-1), dict(flags=2),
+    dict(batch=0), dict(n=0), dict(k=0), dict(k=11), dict(dtype=3), dict(dtype=-1), dict(flags=4),
     dict(n=(1 << 31) + 1, k=1),
     dict(tuning=dict(digit_bits=7)), dict(tuning=dict(digit_bits=13)), dict(tuning=dict(path=4)), dict(tuning=dict(prefilter=2)),
     dict(tuning=dict(prefilter=-2)),
@@ -97,6 +97,22 @@ def test_select_validates_on_the_host_before_launching():
     with pytest.raises(B.RtopkError) as e:
         _select(batch=70000, n=100, k=1, tuning=dict(path=2), ws_bytes=1 << 40)
     assert e.value.status == 1          # rows are a grid dimension in the many-workgroup path
+
+
+def test_sizing_calls_pair_with_the_selection_calls():
+    # the plain sizing call is the _ex call with no tuning; the debug-counters flag is accepted and changes nothing
+    for batch, n, dt in ((1, 1 << 20, 0), (1024, 131072, 2), (3, 5000, 1)):
+        plain = B.rtopk_workspace_bytes(batch, n, 7, dt)
+        assert plain == B.rtopk_workspace_bytes(batch, n, 7, dt, tuning=dict())
+        assert plain == B.rtopk_workspace_bytes(batch, n, 7, dt, flags=B.RTOPK_FLAG_DEBUG_COUNTERS)
+    # a tuning that forces many workgroups per row on a short-row shape needs the candidate arrays: a buffer sized
+    # without the tuning is refused (status 2) before anything is launched, and the message says how to size it
+    small = B.rtopk_workspace_bytes(1024, 131072, 50, 2)
+    forced = B.rtopk_workspace_bytes(1024, 131072, 50, 2, tuning=dict(path=2))
+    assert forced > small
+    with pytest.raises(B.RtopkError) as e:
+        _select(batch=1024, n=131072, k=50, dtype=2, ws_bytes=small, tuning=dict(path=2))
+    assert e.value.status == 2 and "rtopk_workspace_bytes_ex" in str(e.value)
 
 
 def test_topk_wrapper_refuses_cpu_tensors():
