@@ -39,7 +39,9 @@ typedef enum {
     RTOPK_ERR_INVALID_ARG = 1,          /* null pointer, k < 1, k > n, batch < 1, n out of range, bad dtype/flags */
     RTOPK_ERR_WORKSPACE_TOO_SMALL = 2,  /* workspace_bytes below rtopk_workspace_bytes() for these arguments    */
     RTOPK_ERR_UNSUPPORTED = 3,          /* misaligned buffers (see rtopk_select)                                */
-    RTOPK_ERR_HIP = 4                   /* a kernel launch was rejected by the runtime                          */
+    RTOPK_ERR_HIP = 4,                  /* a kernel launch was rejected by the runtime                          */
+    RTOPK_ERR_STATIC_SCRATCH = 5        /* rtopk_select_static: the arguments need more scratch memory than the
+                                           library's built-in buffer holds (use rtopk_select with a workspace)  */
 } rtopk_status;
 
 enum {
@@ -131,6 +133,28 @@ rtopk_status rtopk_select_ex(const void* keys, int64_t batch, int64_t n, int64_t
                              uint32_t flags, uint64_t seed, void* out_values, int64_t* out_indices,
                              void* workspace, size_t workspace_bytes, void* hip_stream,
                              const rtopk_tuning* tuning);
+
+/*
+ * rtopk_select for callers that cannot allocate device memory and have no workspace to pass: code under
+ * HIP graph capture, tight serving loops (top-k over a batch of logit rows at every decoding step),
+ * harnesses that forbid hipMalloc.  Identical to rtopk_select in arguments, defaults, result and error
+ * behaviour, except that the scratch memory is not the caller's: it is a buffer of
+ * RTOPK_STATIC_SCRATCH_BYTES that is part of the library's device code (every GPU the library runs on
+ * holds one copy from the first call on that GPU until the process ends).  The call allocates and frees
+ * nothing and synchronises nothing; the first call on a device looks the buffer's address up once.
+ *
+ * Limits: rtopk_workspace_bytes(batch, n, k, dt, flags) must not exceed RTOPK_STATIC_SCRATCH_BYTES --
+ * otherwise RTOPK_ERR_STATIC_SCRATCH is returned and nothing is launched.  The workspace holds two candidate
+ * arrays of 8 bytes per key, so that admits inputs of up to about 4 million keys in total (batch * n), of any
+ * shape: 32 rows of 2^17 logits, one row of 2^22 keys.
+ * All calls on one GPU share that GPU's buffer: two calls that may overlap in time on the same GPU (different
+ * streams, different host threads) race; the caller orders them.  The buffer keeps the previous call's
+ * contents; every call clears what it needs cleared itself.
+ */
+#define RTOPK_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+rtopk_status rtopk_select_static(const void* keys, int64_t batch, int64_t n, int64_t k, rtopk_dtype dt, int largest,
+                                 uint32_t flags, uint64_t seed, void* out_values, int64_t* out_indices,
+                                 void* hip_stream);
 
 /*
  * Profiling variant of rtopk_select_ex: additionally records caller-created HIP events (hipEvent_t handles,

@@ -29,6 +29,7 @@ EXPORTS = (
     "rtopk_select",
     "rtopk_select_ex",
     "rtopk_select_events",
+    "rtopk_select_static",
     "rtopk_status_string",
     "rtopk_version",
 )
@@ -150,6 +151,8 @@ def load():
         lib.rtopk_select_ex.argtypes = lib.rtopk_select.argtypes + [ctypes.POINTER(RtopkTuning)]
         lib.rtopk_select_events.restype = ctypes.c_int
         lib.rtopk_select_events.argtypes = lib.rtopk_select_ex.argtypes + [ctypes.POINTER(ctypes.c_void_p)]
+        lib.rtopk_select_static.restype = ctypes.c_int
+        lib.rtopk_select_static.argtypes = [vp, i64, i64, i64, ctypes.c_int, ctypes.c_int, u32, u64, vp, vp, vp]
         lib.rtopk_status_string.restype = ctypes.c_char_p
         lib.rtopk_status_string.argtypes = [ctypes.c_int]
         lib.rtopk_version.restype = ctypes.c_char_p
@@ -202,6 +205,18 @@ def rtopk_select(keys_ptr: int, batch: int, n: int, k: int, dtype: int, largest:
         st = load().rtopk_select_events(keys_ptr, batch, n, k, dtype, 1 if largest else 0, flags, seed,
                                         out_values_ptr, out_indices_ptr, workspace_ptr, workspace_bytes, stream,
                                         _tuning_ptr(tuning), arr)
+    if st != RTOPK_OK:
+        raise RtopkError(st, rtopk_status_string(st))
+
+
+RTOPK_STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def rtopk_select_static(keys_ptr: int, batch: int, n: int, k: int, dtype: int, largest: bool, flags: int, seed: int,
+                        out_values_ptr: int, out_indices_ptr: int, stream: int = 0) -> None:
+    """Raw call of the entry point that brings its own scratch memory (no workspace argument, nothing allocated)."""
+    st = load().rtopk_select_static(keys_ptr, batch, n, k, dtype, 1 if largest else 0, flags, seed, out_values_ptr,
+                                    out_indices_ptr, stream)
     if st != RTOPK_OK:
         raise RtopkError(st, rtopk_status_string(st))
 

@@ -1,8 +1,12 @@
 // C-ABI entry points declared in include/rtopk.h: argument validation, the digit plan, workspace layout,
-// and the hand-off to the per-type kernel launchers.  Host code only.
+// and the hand-off to the per-type kernel launchers.  Host code, plus the one device object the library owns:
+// the built-in scratch buffer of rtopk_select_static.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <string.h>
+
+#include <atomic>
+#include <mutex>
 
 #include "rtopk.h"
 #include "rtopk_device.h"
@@ -169,6 +173,31 @@ static Layout make_layout(int64_t batch, int64_t n, const Config& c) {
 
 using namespace rtopk;
 
+// The scratch memory of rtopk_select_static: part of the device code, one copy per GPU.  In host code this
+// name is only a handle for hipGetSymbolAddress; kernels and copies get the address looked up below.
+static __device__ __align__(256) unsigned char scratch[RTOPK_STATIC_SCRATCH_BYTES];
+
+// Address of `scratch` on the current device, looked up once per device (each GPU has its own copy at its own
+// address).  Returns nullptr if the runtime cannot tell.
+static void* static_scratch_of_current_device() {
+    constexpr int kMaxDevices = 64;
+    static std::atomic<void*> known[kMaxDevices];
+    static std::mutex lookup;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    void* p = known[dev].load(std::memory_order_acquire);
+    if (p) return p;
+    std::lock_guard<std::mutex> hold(lookup);
+    p = known[dev].load(std::memory_order_relaxed);
+    if (!p) {
+        void* found = nullptr;
+        if (hipGetSymbolAddress(&found, HIP_SYMBOL(scratch)) != hipSuccess || !found) return nullptr;
+        p = found;
+        known[dev].store(p, std::memory_order_release);
+    }
+    return p;
+}
+
 // How much of a streamed row (its tail) the first sweep reads with cache-allocating loads, for the second sweep
 // to find in the caches (MI355X: 256 MB last-level cache + 32 MB of L2).  Measured on n = 2^28 fp32: the whole call takes
 // 462 us with nothing kept, 449 with 256 MB, 444-445 with 288-320 MB, 451 with 352 MB and more (the first sweep
@@ -185,6 +214,9 @@ const char* rtopk_status_string(rtopk_status s) {
             return "workspace too small for these arguments and tuning (size it with rtopk_workspace_bytes_ex and the same tuning)";
         case RTOPK_ERR_UNSUPPORTED: return "unsupported (misaligned buffer)";
         case RTOPK_ERR_HIP: return "HIP runtime rejected a launch";
+        case RTOPK_ERR_STATIC_SCRATCH:
+            return "these arguments need more scratch memory than the built-in buffer of rtopk_select_static holds "
+                   "(RTOPK_STATIC_SCRATCH_BYTES); use rtopk_select with a caller-owned workspace";
     }
     return "unknown status";
 }
@@ -284,6 +316,22 @@ rtopk_status rtopk_select(const void* keys, int64_t batch, int64_t n, int64_t k,
                           size_t workspace_bytes, void* hip_stream) {
     return rtopk_select_ex(keys, batch, n, k, dt, largest, flags, seed, out_values, out_indices, workspace,
                            workspace_bytes, hip_stream, nullptr);
+}
+
+rtopk_status rtopk_select_static(const void* keys, int64_t batch, int64_t n, int64_t k, rtopk_dtype dt, int largest,
+                                 uint32_t flags, uint64_t seed, void* out_values, int64_t* out_indices,
+                                 void* hip_stream) {
+    size_t need = 0;
+    const rtopk_status sized = rtopk_workspace_bytes(batch, n, k, dt, flags, &need);
+    if (sized != RTOPK_OK) return sized;
+    if (need > RTOPK_STATIC_SCRATCH_BYTES) return RTOPK_ERR_STATIC_SCRATCH;
+    if (!keys || !out_values || !out_indices) return RTOPK_ERR_INVALID_ARG;
+    void* ws = static_scratch_of_current_device();
+    if (!ws) return RTOPK_ERR_HIP;
+    // (every kernel chain starts by clearing the records, histograms and counters it relies on, so what the
+    // previous call left in the buffer does not matter)
+    return rtopk_select(keys, batch, n, k, dt, largest, flags, seed, out_values, out_indices, ws,
+                        RTOPK_STATIC_SCRATCH_BYTES, hip_stream);
 }
 
 }  // extern "C"
