@@ -377,9 +377,15 @@ struct CandSource {
 // set is ever copied, so the compiler can wait for exactly the oldest set instead of draining the queue.
 // The at most two partial tiles are handled afterwards, unpipelined, by fedge(tile).
 // Only tiles in [lo, hi) are visited (for callers that split a row into ranges).
-template <int DEPTH, class Source, class FFull, class FEdge>
+// before_load() runs ahead of every prefetch of the steady state: work that issues stores belongs there.  (The
+// memory counter a wave waits on counts loads and stores alike, in issue order, with a bound fixed at compile
+// time: stores issued after the prefetches would make every wait for a tile also wait for all younger prefetches.)
+struct NoHook {
+    __device__ __forceinline__ void operator()() const {}
+};
+template <int DEPTH, class Source, class FFull, class FEdge, class Hook = NoHook>
 __device__ __forceinline__ void for_each_tile(const Source& src, u32 wg, u32 G, u32 ntiles, FFull&& f, FEdge&& fedge,
-                                              u32 lo = 0u, u32 hi = 0xffffffffu) {
+                                              u32 lo = 0u, u32 hi = 0xffffffffu, Hook&& before_load = Hook()) {
     const u32 tid = threadIdx.x;
     u32 f0, f1;  // tiles [f0, f1) are full
     src.full_range(f0, f1);
@@ -395,23 +401,35 @@ __device__ __forceinline__ void for_each_tile(const Source& src, u32 wg, u32 G, 
     if (m != 0) {
         if constexpr (DEPTH == 2) {
             typename Source::Tile a, b, c;
-            src.load_full(tile_at(0), tid, a);
-            if (m > 1) src.load_full(tile_at(1), tid, b);
             u32 i = 0;
-            // steady state: all three loads of a round exist, so every load is unconditional
-            for (; i + 4 < m; i += 3) {
-                src.load_full(tile_at(i + 2), tid, c);
+            if (m > 4) {
+                // Both loads that the steady state finds in flight are issued unconditionally right before it, and
+                // nothing that uses a tile may be scheduled ahead of the prefetch that precedes it in program order:
+                // then the compiler's bound on outstanding loads at each use is the steady state's own (two tiles
+                // stay in flight while one is processed).
+                src.load_full(tile_at(0), tid, a);
+                src.load_full(tile_at(1), tid, b);
+                for (; i + 4 < m; i += 3) {
+                    before_load();
+                    src.load_full(tile_at(i + 2), tid, c);
+                    __builtin_amdgcn_sched_barrier(0);
+                    f(a);
+                    before_load();
+                    src.load_full(tile_at(i + 3), tid, a);
+                    __builtin_amdgcn_sched_barrier(0);
+                    f(b);
+                    before_load();
+                    src.load_full(tile_at(i + 4), tid, b);
+                    __builtin_amdgcn_sched_barrier(0);
+                    f(c);
+                }
+                // tiles i and i + 1 are loaded; at most two more follow
                 f(a);
-                src.load_full(tile_at(i + 3), tid, a);
                 f(b);
-                src.load_full(tile_at(i + 4), tid, b);
-                f(c);
+                i += 2;
             }
-            // at most four tiles left; a (and b, if it exists) are loaded
-            f(a);
-            if (i + 1 < m) f(b);
-            for (u32 j = i + 2; j < m; ++j) {
-                src.load_full(tile_at(j), tid, a);
+            for (; i < m; ++i) {
+                src.load_full(tile_at(i), tid, a);
                 f(a);
             }
         } else if constexpr (DEPTH == 1) {
@@ -419,8 +437,10 @@ __device__ __forceinline__ void for_each_tile(const Source& src, u32 wg, u32 G, 
             src.load_full(tile_at(0), tid, a);
             u32 i = 0;
             for (; i + 2 < m; i += 2) {
+                before_load();
                 src.load_full(tile_at(i + 1), tid, b);
                 f(a);
+                before_load();
                 src.load_full(tile_at(i + 2), tid, a);
                 f(b);
             }

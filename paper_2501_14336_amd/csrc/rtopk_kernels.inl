@@ -64,8 +64,14 @@ constexpr int kRowBlock = 1024;               // threads per workgroup, one-work
 constexpr int kVecs = RTOPK_VECS;             // 16-byte loads per lane per tile (candidate arrays, fp32 rows)
 template <int DT> constexpr int key_vecs() { return DT == RTOPK_F32 ? RTOPK_VECS : RTOPK_VECS / 2; }  // 16 elements per lane
 
-template <int B>
+constexpr int kStage = 2 * kStageCap;      // entries per wave in the staging area
+constexpr int kStageGroup = 4;             // slots of a tile between two looks at the fill level (at most 64 entries each)
+
+// ST: entries per wave in the staging area.  kStage by default; the sweep that filters a streamed row stages more
+// when one workgroup has a compute unit's LDS to itself (see k_prefilter_keys).
+template <int B, int ST = kStage>
 struct Shared {
+    static constexpr int kStageEntries = ST;
     u32 hist[kMaxBins];
     u32 wsum[B / 64];
     u32 red[2 * (B / 64)];
@@ -73,13 +79,12 @@ struct Shared {
     float a_s;                        // the row's scaling constant, broadcast by the thread that drew it
     u32 runW, runC;                   // next free output / candidate position of this workgroup's range
     union {
-        struct {
-            uint2 wbuf[B / 64][kStageCap];  // per-wave staged winners    (raw bits, index)
-            uint2 cbuf[B / 64][kStageCap];  // per-wave staged candidates (raw bits, index)
-        };
+        // per-wave staging area of (raw bits, index) entries: winners are stacked from the bottom up,
+        // candidates from the top down, so either kind may use what the other leaves free
+        uint2 stage[B / 64][ST];
         // the same bytes while nothing is staged: interleaved copies of the histogram a single workgroup
         // builds of its whole row
-        u32 wide[4 * (B / 64) * kStageCap + 32];
+        u32 wide[2 * (B / 64) * ST + 32];
     };
 };
 
@@ -187,8 +192,8 @@ __device__ __forceinline__ Selection select_from_counts(Count&& count, int nb, u
 // selectBin for pass entry e, plus the housekeeping that fits between its barriers: the LDS histogram is
 // cleared for the next digit's counts and the workgroup's running write positions start at the row's
 // (a workgroup that shares the row adds its own offsets afterwards).
-template <int B, class Count>
-__device__ __forceinline__ Selection select_pass(Count&& count, int nb, const PassEntry& e, Shared<B>& sm,
+template <int B, class Count, int ST>
+__device__ __forceinline__ Selection select_pass(Count&& count, int nb, const PassEntry& e, Shared<B, ST>& sm,
                                                  rtopk_row_trace* st, bool* distrust = nullptr) {
     return select_from_counts<B>(
         count, nb, e.k_rem, sm, st,
@@ -607,7 +612,7 @@ __device__ __forceinline__ Lds<u64>* lds_words(const uint2* p) { return (Lds<u64
 __device__ __forceinline__ Lds<u32>* lds_word(u32* p) { return (Lds<u32>*)p; }
 
 template <int DT>
-__device__ __noinline__ void flush_wave_winners(void* out_v, long long* out_i, u32 kk, Lds<u64>* buf, Lds<u32>* run,
+__device__ __forceinline__ void flush_winners_body(void* out_v, long long* out_i, u32 kk, Lds<u64>* buf, Lds<u32>* run,
                                                    u32 fill, u32 lane) {
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     u32 base = 0;
@@ -626,6 +631,11 @@ __device__ __noinline__ void flush_wave_winners(void* out_v, long long* out_i, u
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
 }
+template <int DT>
+__device__ __noinline__ void flush_wave_winners(void* out_v, long long* out_i, u32 kk, Lds<u64>* buf, Lds<u32>* run,
+                                                u32 fill, u32 lane) {
+    flush_winners_body<DT>(out_v, out_i, kk, buf, run, fill, lane);
+}
 // What the candidate flush needs to count the next pass's digit (countBin of pass p + 1 happens here, on
 // full waves, rather than element by element in the sweep).
 struct NextCount {
@@ -633,29 +643,40 @@ struct NextCount {
     PassInfo pi;
     u32 dirmask, idx_max;
     float a_s;
+    // the prefilter sweep that counts by raw bits (prefilter_tile_raw) leaves its NaN bookkeeping to the write-back:
+    bool nan_fix = false;   // move the count of every staged NaN from the raw bin of its bits to the NaNs' own bin
+    bool discard = false;   // ... and write nothing (the prefilter declined: what is staged is staged for this only)
+    u32 nan_hist_shift = 0, nan_bin = 0;
 };
+enum : u32 { kFlushToList = 1u, kFlushCount = 2u, kFlushNanFix = 4u, kFlushDiscard = 8u };
 
-// to_list: the candidates go to the LDS list cand_lds instead of cand_out; count: the next pass's digit, described
-// by (src, shift, bits, dirmask, idx_max, a_s), is counted into the LDS histogram hist.  (Flags, not null tests:
-// an LDS pointer to the start of the workgroup's LDS is the number 0, and a null generic pointer casts to -1.)
+// what (kFlush* bits): to-list -- the candidates go to the LDS list cand_lds instead of cand_out; count -- the next
+// pass's digit, described by (src, shift, bits, dirmask, idx_max, a_s), is counted into the LDS histogram hist;
+// NaN-fix -- hist is the CURRENT pass's raw-bit histogram (prefilter_tile_raw), shift its digit's shift and idx_max
+// the bin all NaNs share: every staged NaN's count is moved there; discard -- nothing is written.
+// (Flags, not null tests: an LDS pointer to the start of the workgroup's LDS is the number 0, and a null generic
+// pointer casts to -1.)
 template <int DT>
-__device__ __noinline__ void flush_wave_candidates(uint2* cand_out, Lds<u64>* cand_lds, u32 ncap, Lds<u64>* buf,
-                                                   Lds<u32>* run, u32 fill, u32 lane, Lds<u32>* hist, u32 src, u32 shift,
-                                                   u32 bits, u32 dirmask, u32 idx_max, float a_s, bool to_list, bool count) {
+__device__ __forceinline__ void flush_candidates_body(uint2* cand_out, Lds<u64>* cand_lds, u32 ncap, Lds<u64>* buf,
+                                                      Lds<u32>* run, u32 fill, u32 lane, Lds<u32>* hist, u32 src, u32 shift,
+                                                      u32 bits, u32 dirmask, u32 idx_max, float a_s, u32 what) {
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     u32 base = 0;
-    if (lane == 0) base = __hip_atomic_fetch_add(run, fill, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-    base = __builtin_amdgcn_readfirstlane(base);
+    if (!(what & kFlushDiscard)) {
+        if (lane == 0) base = __hip_atomic_fetch_add(run, fill, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        base = __builtin_amdgcn_readfirstlane(base);
+    }
     const PassInfo pi{src, shift, bits};
     for (u32 i = lane; i < fill; i += 64) {
         const u64 e = buf[i];
         const u32 pos = base + i;
-        if (to_list) {
+        if (what & kFlushDiscard) {
+        } else if (what & kFlushToList) {
             if (pos < kRankCap) cand_lds[pos] = e;
         } else if (pos < ncap) {
             ((Glb<u64>*)cand_out)[pos] = e;
         }
-        if (count) {
+        if (what & kFlushCount) {
             // as hist_add: the lanes that hold the first active lane's digit share one LDS atomic
             const u32 dg = digit_of<DT, SRC_RUNTIME>(pi, (u32)e, (u32)(e >> 32), dirmask, idx_max, a_s);
             const u32 d0 = __builtin_amdgcn_readfirstlane(dg);
@@ -665,42 +686,93 @@ __device__ __noinline__ void flush_wave_candidates(uint2* cand_out, Lds<u64>* ca
             if (!same || leader)
                 __hip_atomic_fetch_add(hist + dg, same ? (u32)__popcll(m) : 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         }
+        if (DT == RTOPK_F32 && (what & kFlushNanFix)) {
+            const u32 raw = (u32)e;
+            if ((raw & 0x7fffffffu) > 0x7f800000u) {
+                __hip_atomic_fetch_add(hist + (raw >> shift), ~0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                __hip_atomic_fetch_add(hist + idx_max, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            }
+        }
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
 }
-
 template <int DT>
-__device__ __forceinline__ void flush_winners(const ClassifyOut<DT>& o, const uint2* buf, u32* run, u32 fill, u32 lane) {
-    flush_wave_winners<DT>(o.out_v, o.out_i, o.kk, lds_words(buf), lds_word(run), fill, lane);
+__device__ __noinline__ void flush_wave_candidates(uint2* cand_out, Lds<u64>* cand_lds, u32 ncap, Lds<u64>* buf,
+                                                   Lds<u32>* run, u32 fill, u32 lane, Lds<u32>* hist, u32 src, u32 shift,
+                                                   u32 bits, u32 dirmask, u32 idx_max, float a_s, u32 what) {
+    flush_candidates_body<DT>(cand_out, cand_lds, ncap, buf, run, fill, lane, hist, src, shift, bits, dirmask, idx_max, a_s,
+                              what);
 }
-template <int DT>
+
+// INLINE: the write-back is expanded in place.  A call costs more than its instructions: a function starts by
+// waiting for every outstanding memory operation of the wave, so each call made in the middle of a sweep drains
+// the tiles the wave has prefetched.  The sweeps that stream from memory therefore look at the fill level only
+// every kStageGroup slots and expand the write-back at those few places; calls remain where nothing is in flight
+// (the sweep over a row held in registers) and for what is left at the end of a sweep.
+template <int DT, bool INLINE = false>
+__device__ __forceinline__ void flush_winners(const ClassifyOut<DT>& o, const uint2* buf, u32* run, u32 fill, u32 lane) {
+    if constexpr (INLINE)
+        flush_winners_body<DT>(o.out_v, o.out_i, o.kk, lds_words(buf), lds_word(run), fill, lane);
+    else
+        flush_wave_winners<DT>(o.out_v, o.out_i, o.kk, lds_words(buf), lds_word(run), fill, lane);
+}
+template <int DT, bool INLINE = false>
 __device__ __forceinline__ void flush_candidates(const ClassifyOut<DT>& o, const uint2* buf, u32* run, u32 fill, u32 lane,
                                                  const NextCount& nc) {
-    flush_wave_candidates<DT>(o.cand_out, lds_words(o.cand_lds), o.ncap, lds_words(buf), lds_word(run), fill, lane,
-                              lds_word(nc.hist.h), nc.pi.src, nc.pi.shift, nc.pi.bits, nc.dirmask, nc.idx_max, nc.a_s,
-                              o.cand_lds != nullptr, nc.hist.h != nullptr);
+    const u32 what = (o.cand_lds != nullptr ? kFlushToList : 0u) | (nc.hist.h != nullptr && !nc.nan_fix ? kFlushCount : 0u) |
+                     (nc.nan_fix ? kFlushNanFix : 0u) | (nc.discard ? kFlushDiscard : 0u);
+    const u32 shift = nc.nan_fix ? nc.nan_hist_shift : nc.pi.shift;
+    const u32 imax = nc.nan_fix ? nc.nan_bin : nc.idx_max;
+    if constexpr (INLINE)
+        flush_candidates_body<DT>(o.cand_out, lds_words(o.cand_lds), o.ncap, lds_words(buf), lds_word(run), fill, lane,
+                                  lds_word(nc.hist.h), nc.pi.src, shift, nc.pi.bits, nc.dirmask, imax, nc.a_s, what);
+    else
+        flush_wave_candidates<DT>(o.cand_out, lds_words(o.cand_lds), o.ncap, lds_words(buf), lds_word(run), fill, lane,
+                                  lds_word(nc.hist.h), nc.pi.src, shift, nc.pi.bits, nc.dirmask, imax, nc.a_s, what);
 }
 
-// Entries waiting in this wave's LDS buffers (wave-uniform).
+// Entries waiting in this wave's staging area (wave-uniform): winners in [0, fillW), candidates in
+// [ST - fillC, ST), ST being the area's size.
 struct WriteState {
     u32 fillW, fillC;
 };
 
-// One tile, one sweep over its slots: classify, append survivors to the wave's buffers.
-// RARE: survivors are expected to be few (fully unrolled callers: keeps the append code off the straight path).
+// Write back whatever is staged.
+template <int DT, bool INLINE, int B, int ST>
+__device__ __forceinline__ void flush_staged(const ClassifyOut<DT>& o, Shared<B, ST>& sm, u32 lane, u32 wave, WriteState& ws,
+                                             const NextCount& nc) {
+    uint2* st = sm.stage[wave];
+    if (ws.fillW) flush_winners<DT, INLINE>(o, st, &sm.runW, ws.fillW, lane);
+    if (ws.fillC) flush_candidates<DT, INLINE>(o, st + (ST - ws.fillC), &sm.runC, ws.fillC, lane, nc);
+    ws.fillW = ws.fillC = 0;
+}
+// Before a group of kStageGroup slots: make room for everything the group can add.
+template <int DT, bool INLINE = true, int B, int ST>
+__device__ __forceinline__ void make_room(const ClassifyOut<DT>& o, Shared<B, ST>& sm, u32 lane, u32 wave, WriteState& ws,
+                                          const NextCount& nc) {
+    if (ws.fillW + ws.fillC > (u32)(ST - 64 * kStageGroup)) flush_staged<DT, INLINE>(o, sm, lane, wave, ws, nc);
+}
+// Between two tiles of a streaming sweep, before the next prefetch is issued (see for_each_tile): the place where a
+// write-back costs least, so what has piled up goes out here already at a slightly lower fill level.
+constexpr u32 kStageEarlyRoom = 320;
+
+// One tile, one sweep over its slots: classify, append survivors to the wave's staging area.
+// RARE: survivors are expected to be few and nothing is being prefetched (the row held in registers, fully
+// unrolled): the append code is kept off the straight path and the write-back is a call, made when fewer than 64
+// entries are free.
 template <bool FULL, bool FLOATCMP, class Source, int DT, int SRC, int B, bool RARE = false, bool PRE = false,
-          bool MERGE = false>
+          bool MERGE = false, int ST = kStage>
 __device__ __forceinline__ void classify_tile(const Source& src, const typename Source::Tile& t, const DigitCtx& c,
-                                              const ClassifyOut<DT>& o, Shared<B>& sm, u32 lane, u32 wave,
+                                              const ClassifyOut<DT>& o, Shared<B, ST>& sm, u32 lane, u32 wave,
                                               WriteState& ws, const NextCount& nc) {
     constexpr int E = Source::E;
     constexpr int S = Source::kSlots;
-    uint2* wbuf = sm.wbuf[wave];
-    uint2* cbuf = sm.cbuf[wave];
+    uint2* st = sm.stage[wave];
     const u64 me_bit = 1ull << lane;
     // (the prefilter sweep counts every element; MERGE: lanes that share the first lane's digit merge their adds)
 #pragma unroll
     for (int s = 0; s < S; ++s) {
+        if (!RARE && s % kStageGroup == 0) make_room<DT>(o, sm, lane, wave, ws, nc);
         u64 mw, mc;
         if constexpr (PRE)
             slot_masks<FULL, FLOATCMP, Source, DT, SRC, PRE, MERGE>(src, t, s, c, o, mw, mc, HistSlot{sm.hist}, lane);
@@ -712,21 +784,54 @@ __device__ __forceinline__ void classify_tile(const Source& src, const typename 
             bool valid;
             src.get(t, s, raw, idx, valid);
             if (mw) {
-                if (mw & me_bit) wbuf[ws.fillW + mbcnt64(mw)] = make_uint2(raw, idx);
+                if (mw & me_bit) st[ws.fillW + mbcnt64(mw)] = make_uint2(raw, idx);
                 ws.fillW += (u32)__popcll(mw);
-                if (ws.fillW > (u32)(kStageCap - 64)) {
-                    flush_winners<DT>(o, wbuf, &sm.runW, ws.fillW, lane);
-                    ws.fillW = 0;
-                }
             }
             if (mc) {
-                if (mc & me_bit) cbuf[ws.fillC + mbcnt64(mc)] = make_uint2(raw, idx);
+                if (mc & me_bit) st[(u32)(ST - 1) - (ws.fillC + mbcnt64(mc))] = make_uint2(raw, idx);
                 ws.fillC += (u32)__popcll(mc);
-                if (ws.fillC > (u32)(kStageCap - 64)) {
-                    flush_candidates<DT>(o, cbuf, &sm.runC, ws.fillC, lane, nc);
-                    ws.fillC = 0;
-                }
             }
+            if (RARE && ws.fillW + ws.fillC > (u32)(ST - 64)) flush_staged<DT, false>(o, sm, lane, wave, ws, nc);
+        }
+    }
+}
+
+// One tile of the prefilter sweep over fp32 keys, the cheap way.  countBin needs only the element's raw top bits
+// (hist_tile_raw: the bins are renamed afterwards), and "digit >= bound" is one float comparison with the number at
+// the bound's edge (o.t2), so the straight path is a shift, an LDS add and a compare per element.  The comparison
+// is written so that a NaN passes it in either direction: whatever passes is staged and nothing else is done here
+// (each further instruction on this path is paid in 4 of 10 slots at 1 % kept) -- the write-back moves every NaN's
+// count from the raw bin its bits fell in to the one bin all NaNs share, raw bin 2^bits/2 - 1 (the top of the
+// positive half: its key digit is the best for "largest", the worst for "smallest").  For "smallest" the NaNs are
+// kept although they rank below the bound; pass 0 drops them like anything else below the k-th key's bin.  When
+// the prefilter declined, the edge is an infinity: only NaNs (and infinities of one sign) are staged, to have
+// their counts moved, and nothing is written.
+template <bool FULL, bool MERGE, bool LARGEST, class Source, int B, int ST>
+__device__ __forceinline__ void prefilter_tile_raw(const Source& src, const typename Source::Tile& t, const DigitCtx& c,
+                                                   const ClassifyOut<RTOPK_F32>& o, Shared<B, ST>& sm, u32 lane, u32 wave,
+                                                   WriteState& ws, const NextCount& nc) {
+    static_assert(Source::E == 4, "fp32 keys");
+    constexpr int S = Source::kSlots;
+    uint2* st = sm.stage[wave];
+    const u64 me_bit = 1ull << lane;
+    const HistSlot hs{sm.hist};
+#pragma unroll
+    for (int s = 0; s < S; ++s) {
+        // (sparse by design: the room made between tiles nearly always suffices, so this one may be a call)
+        if (s % kStageGroup == 0) make_room<RTOPK_F32, false>(o, sm, lane, wave, ws, nc);
+        u32 raw, idx;
+        bool valid;
+        src.get(t, s, raw, idx, valid);  // (full tiles: raw is a register, idx and valid are not computed unless used)
+        const u32 draw = raw >> c.pi.shift;
+        if (FULL || valid) {
+            if (MERGE) hist_add(hs, draw, lane); else hist_add_plain(hs, draw);
+        }
+        const float x = __uint_as_float(raw);
+        u64 m = ballot64(LARGEST ? !(x < o.t2) : !(x >= o.t2));
+        if (!FULL) m &= ballot64(valid);
+        if (m) {
+            if (m & me_bit) st[(u32)(ST - 1) - (ws.fillC + mbcnt64(m))] = make_uint2(raw, idx);
+            ws.fillC += (u32)__popcll(m);
         }
     }
 }
@@ -743,9 +848,9 @@ enum { HIST_IN_LDS = 0, HIST_IN_GLOBAL = 1 };
 // of a bin >= sel.bin goes to the candidate array (into a segment of fixed position: there are no counts yet to
 // derive exact offsets from), and this same first digit is counted for EVERY element of X, kept or not (the
 // exact histogram pass 0 selects on, and the per-workgroup records either kind of pass 0 takes its offsets from).
-template <class Source, int DT, int SRC, int B, bool SINGLE, class Resident = NoResident, bool PRE = false>
+template <class Source, int DT, int SRC, int B, bool SINGLE, class Resident = NoResident, bool PRE = false, int ST = kStage>
 __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Params& P, int p, int row, u32 wg, u32 G,
-                                                    const PassEntry& e, rtopk_row_trace* st, float a_s, Shared<B>& sm,
+                                                    const PassEntry& e, rtopk_row_trace* st, float a_s, Shared<B, ST>& sm,
                                                     u32 where, const Selection& sel, u32 records, bool own_segment,
                                                     const Resident& resident = Resident()) {
     constexpr bool kResident = !std::is_same<Resident, NoResident>::value;
@@ -847,6 +952,24 @@ __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Par
         }
     }
 
+    // The prefilter sweep over fp32 keys: raw-bit counting and one float comparison with the bound's edge, whenever
+    // that edge is a number (not at the boundary between the zeros, not among the NaNs).  A bound above every bin
+    // (the prefilter declined) keeps nothing: the edge is then an infinity no kept-test passes but NaNs'.
+    bool raw_pre = false, keep_none = false;
+    if constexpr (PRE && DT == RTOPK_F32 && SRC == SRC_KEY) {
+        const bool largest = P.dirmask == 0;
+        const u32 maxd = (1u << ctx.pi.bits) - 1u;
+        if (ctx.pi.shift + ctx.pi.bits == 32u) {
+            if (sel.bin > maxd) {
+                raw_pre = keep_none = true;
+                o.t2 = largest ? __builtin_inff() : -__builtin_inff();
+            } else {
+                const u64 Bo = largest ? sel.bin : maxd - sel.bin;
+                raw_pre = threshold_number<DT>((largest ? Bo : Bo + 1u) << ctx.pi.shift, &o.t2);
+            }
+        }
+    }
+
     if (!SINGLE) {
         if (tid == 0) {
             sm.runW = runW;
@@ -866,6 +989,13 @@ __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Par
     nc.dirmask = ctx.dirmask;
     nc.idx_max = ctx.idx_max;
     nc.a_s = ctx.a_s;
+    if (raw_pre) {
+        nc.hist = HistSlot{sm.hist};
+        nc.nan_fix = true;
+        nc.discard = keep_none;
+        nc.nan_hist_shift = ctx.pi.shift;
+        nc.nan_bin = (1u << (ctx.pi.bits - 1u)) - 1u;
+    }
     if constexpr (kResident && SRC != SRC_RUNTIME) {
         resident([&](const typename Source::Tile& cur) __attribute__((always_inline)) {
             if (cur.full && floatcmp)
@@ -875,9 +1005,24 @@ __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Par
         });
     } else
     // tiles of X are dealt round-robin to the row's workgroups; a candidate segment belongs to one workgroup
-    for_each_tile<SINGLE ? 1 : 2>(
+    // (one tile prefetched while one is processed; the sweeps that write into the stream of reads measured faster
+    // that way than with two)
+    for_each_tile<SINGLE || PRE ? 1 : 2>(
         src, own_segment ? 0u : wg, own_segment ? 1u : G, ntiles,
         [&](const typename Source::Tile& cur) {
+            if constexpr (PRE && DT == RTOPK_F32 && SRC == SRC_KEY) {
+                if (raw_pre) {
+                    const bool hot = hot_lanes<Source, DT, SRC>(src, cur, ctx) >= 12u;
+                    if (P.dirmask == 0) {
+                        if (hot) prefilter_tile_raw<true, true, true, Source>(src, cur, ctx, o, sm, lane, wave, ws, nc);
+                        else prefilter_tile_raw<true, false, true, Source>(src, cur, ctx, o, sm, lane, wave, ws, nc);
+                    } else {
+                        if (hot) prefilter_tile_raw<true, true, false, Source>(src, cur, ctx, o, sm, lane, wave, ws, nc);
+                        else prefilter_tile_raw<true, false, false, Source>(src, cur, ctx, o, sm, lane, wave, ws, nc);
+                    }
+                    return;
+                }
+            }
             if constexpr (PRE) {
                 // merged adds when the tile's digits are seen to pile up, as in the HIST sweep
                 if (hot_lanes<Source, DT, SRC>(src, cur, ctx) >= 12u)
@@ -894,10 +1039,20 @@ __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Par
             }
         },
         [&](const typename Source::Tile& cur) {
+            if constexpr (PRE && DT == RTOPK_F32 && SRC == SRC_KEY) {
+                if (raw_pre) {
+                    if (P.dirmask == 0) prefilter_tile_raw<false, true, true, Source>(src, cur, ctx, o, sm, lane, wave, ws, nc);
+                    else prefilter_tile_raw<false, true, false, Source>(src, cur, ctx, o, sm, lane, wave, ws, nc);
+                    return;
+                }
+            }
             classify_tile<false, false, Source, DT, SRC, B, false, PRE, true>(src, cur, ctx, o, sm, lane, wave, ws, nc);
+        },
+        0u, 0xffffffffu,
+        [&]() __attribute__((always_inline)) {
+            if (ws.fillW + ws.fillC > (u32)ST - kStageEarlyRoom) flush_staged<DT, true>(o, sm, lane, wave, ws, nc);
         });
-    if (ws.fillW) flush_winners<DT>(o, sm.wbuf[wave], &sm.runW, ws.fillW, lane);
-    if (ws.fillC) flush_candidates<DT>(o, sm.cbuf[wave], &sm.runC, ws.fillC, lane, nc);
+    flush_staged<DT, false>(o, sm, lane, wave, ws, nc);
 
 #ifdef RTOPK_TIMING
     t_sweep = wall_clock64();
@@ -907,6 +1062,23 @@ __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Par
         // publish the next pass's histogram: LDS -> global (agent-scope atomics), then the suffix sums the
         // next CLASSIFY needs for its offsets, and the segment of the candidate array this workgroup wrote
         __syncthreads();
+        if (raw_pre) {
+            // the sweep counted by raw top bits: move every count to the bin of its key digit
+            constexpr int kPer = kMaxBins / B;
+            u32 v[kPer];
+#pragma unroll
+            for (int i = 0; i < kPer; ++i) {
+                const int j = (int)tid + i * B;
+                v[i] = j < nb_next ? sm.hist[j] : 0u;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int i = 0; i < kPer; ++i) {
+                const int j = (int)tid + i * B;
+                if (j < nb_next) sm.hist[key_digit_of_raw((u32)j, next_pi.bits, P.dirmask == 0)] = v[i];
+            }
+            __syncthreads();
+        }
         if (!SINGLE) {
             u32* gnext = P.ghist + ((size_t)(pn % 3) * P.batch + row) * kMaxBins;
             for (int j = tid; j < nb_next; j += B) {
@@ -1027,9 +1199,15 @@ __global__ void __launch_bounds__(kGridBlock) k_classify_keys(Params P) {
 // pass: X is read once instead of twice.  When the exact counts put the k-th key's bin below the bound, pass 0
 // is the ordinary CLASSIFY sweep over X instead (k_pass0_after_prefilter decides); the result never depends on
 // the sample.
-template <int DT, int SRC, bool NT>
+// BIG: the launch puts at most one workgroup on a compute unit, so each wave can stage three times as much
+// before it has to write.  That matters more than its size suggests: a wave's stores and its prefetches share one
+// in-order completion counter, so every write-back in mid-sweep holds the wave until the stores are acknowledged
+// (config 4, 0.85 % of the row kept: about six write-backs per wave cost 25 us of a 190 us sweep; with room for
+// 1536 entries nearly everything a wave keeps leaves in one piece when its sweep has ended).
+constexpr int kStageBig = 1536;
+template <int DT, int SRC, bool NT, bool BIG>
 __global__ void __launch_bounds__(kGridBlock) k_prefilter_keys(Params P) {
-    __shared__ Shared<kGridBlock> sm;
+    __shared__ Shared<kGridBlock, BIG ? kStageBig : kStage> sm;
     const int row = blockIdx.y;
     rtopk_row_trace* st = row_state(P, row);
     PassEntry e = pass_entry(P, st, 0);
@@ -1659,14 +1837,22 @@ static rtopk_status launch_all(const Params& P, const Config& c, bool scaled, hi
     const bool nt = (P.flags & kInternalStream) != 0;
     if (c.prefilter) {
         // the sample's histogram, then the prefilter sweep (never scaled: make_config)
+        // (fp32 rows swept by at most one workgroup per compute unit: the variant that stages more per wave)
+        const bool big = DT == RTOPK_F32 && (long long)c.G * batch <= 256;
         if (nt) {
             hipLaunchKernelGGL((k_hist_keys<DT, SRC_KEY, true>), grid, block, 0, st, P);
             mark(events, 2, st);
-            hipLaunchKernelGGL((k_prefilter_keys<DT, SRC_KEY, true>), grid, block, 0, st, P);
+            if constexpr (DT == RTOPK_F32) {
+                if (big) hipLaunchKernelGGL((k_prefilter_keys<DT, SRC_KEY, true, true>), grid, block, 0, st, P);
+            }
+            if (!big) hipLaunchKernelGGL((k_prefilter_keys<DT, SRC_KEY, true, false>), grid, block, 0, st, P);
         } else {
             hipLaunchKernelGGL((k_hist_keys<DT, SRC_KEY, false>), grid, block, 0, st, P);
             mark(events, 2, st);
-            hipLaunchKernelGGL((k_prefilter_keys<DT, SRC_KEY, false>), grid, block, 0, st, P);
+            if constexpr (DT == RTOPK_F32) {
+                if (big) hipLaunchKernelGGL((k_prefilter_keys<DT, SRC_KEY, false, true>), grid, block, 0, st, P);
+            }
+            if (!big) hipLaunchKernelGGL((k_prefilter_keys<DT, SRC_KEY, false, false>), grid, block, 0, st, P);
         }
     } else if (scaled && nt) {
         hipLaunchKernelGGL((k_hist_keys<DT, kScaledSrc, true>), grid, block, 0, st, P);
