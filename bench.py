@@ -123,6 +123,10 @@ def main() -> int:
         later = sum(8 * p.cand_before + 8 * p.cand_after + (es + 8) * p.winners for p in tr.passes)
         if tr.pre_missed:
             later += (es - 8) * n
+        if tr.pre_merged:
+            # pass 0 read and wrote nothing of its own (its winners leave in pass 1's sweep, which reads all that
+            # was kept, not only pass 0's bin)
+            later += -8 * tr.passes[0].cand_before - 8 * tr.passes[0].cand_after + 8 * (kept - tr.passes[1].cand_before)
         names = ("hist_keys_sample", "prefilter_keys")
     else:
         hist_bytes = es * n                                               # first-pass HIST reads X once

@@ -201,7 +201,11 @@ typedef struct {
                                   2: the same on purpose -- the sample showed the keys crowded into the
                                   bins to keep (over 1/8 of the row; 1/16 for 16-bit keys), so the sweep kept nothing
                                   (pre_bound is the bin count) and only counted                     */
-    uint32_t reserved[8];
+    uint32_t pre_merged;       /* 1: the prefilter's bound bin was the k-th key's bin, and pass 0 had no
+                                  sweep of its own -- pass 1's sweep over what was kept classified by both
+                                  digits at once (pass 0's record: its selectBin; winners are what lay above
+                                  its bin; neither read nor wrote anything)                           */
+    uint32_t reserved[7];
     struct {
         uint32_t where;        /* 0 pass not run; 1 many workgroups; 2 single-workgroup finish;
                                   3 fused one-workgroup-per-row kernel; 4 one-sweep row kernel       */
@@ -211,8 +215,9 @@ typedef struct {
         uint32_t winners;      /* elements sent to the output by this pass                           */
         uint32_t out_before;   /* outputs already written when this pass started                     */
         uint32_t cand_before;  /* candidates this pass looked at                                     */
-        uint32_t window;       /* source | shift << 8 | bits << 16; source 0 scaled key, 1 key,
-                                  2 index (tie break); the digit is bits [shift, shift + bits).
+        uint32_t window;       /* source | shift << 8 | bits << 16 | array << 24; source 0 scaled key, 1 key,
+                                  2 index (tie break); the digit is bits [shift, shift + bits); array: which
+                                  of the two candidate arrays the pass wrote.
                                   Source 3: not a digit pass -- at most 512 candidates were left and
                                   were ranked against each other directly (by key, then index),
                                   which stands for all the digit passes that would have followed;

@@ -61,9 +61,13 @@ class _PassRec(ctypes.Structure):
     def bits(self):
         return (self.window >> 16) & 0xFF
 
+    @property
+    def array(self):
+        return (self.window >> 24) & 1
+
 
 class RtopkRowTrace(ctypes.Structure):
-    _fields_ = [("a_s", ctypes.c_float), ("error", ctypes.c_uint32), ("redo", ctypes.c_uint32), ("redo_why", ctypes.c_uint32), ("pre_elems", ctypes.c_uint32), ("pre_bound", ctypes.c_uint32), ("pre_kept", ctypes.c_uint32), ("pre_missed", ctypes.c_uint32), ("reserved", ctypes.c_uint32 * 8),
+    _fields_ = [("a_s", ctypes.c_float), ("error", ctypes.c_uint32), ("redo", ctypes.c_uint32), ("redo_why", ctypes.c_uint32), ("pre_elems", ctypes.c_uint32), ("pre_bound", ctypes.c_uint32), ("pre_kept", ctypes.c_uint32), ("pre_missed", ctypes.c_uint32), ("pre_merged", ctypes.c_uint32), ("reserved", ctypes.c_uint32 * 7),
                 ("pass_rec", _PassRec * RTOPK_TRACE_MAX_PASSES)]
 
     @property

@@ -154,11 +154,11 @@ static Layout make_layout(int64_t batch, int64_t n, const Config& c) {
     // global histograms, per-workgroup records and segments exist only when several workgroups share a row
     const size_t shared_rows = c.path == 2 ? (size_t)batch : 0;
     L.ghist_off = off;
-    off = align_up(off + (size_t)3 * shared_rows * kMaxBins * 4, 256);
+    off = align_up(off + (size_t)kHostHistBuffers * shared_rows * kMaxBins * 4, 256);
     L.seg_off = off;
     off = align_up(off + (size_t)2 * shared_rows * c.G * 2 * 4, 256);
     L.swg_off = off;
-    off = align_up(off + (size_t)2 * shared_rows * c.G * kSwgStride * 4, 256);
+    off = align_up(off + (size_t)kHostSwgBuffers * shared_rows * c.G * kSwgStride * 4, 256);
     // (the prefilter's per-workgroup segments are laid out by whole tiles: up to two tiles beyond n)
     L.cand_stride = (size_t)n + (c.prefilter ? (size_t)2 * kHostGridBlock * kHostElemsPerLane : 0);
     L.cand0_off = off;

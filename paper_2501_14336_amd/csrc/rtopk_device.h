@@ -31,9 +31,9 @@ struct Params {
     void* out_values;        // Y values, [batch][k]
     long long* out_indices;  // Y indices, [batch][k]
     rtopk_row_trace* state;  // per-row loop state + trace, stride RTOPK_TRACE_STRIDE bytes
-    u32* ghist;              // [3][batch][kMaxBins]  global histograms; pass p reads buffer p % 3, fills (p+1) % 3, clears (p+2) % 3
-    u32* seg;                // [2][batch][G][2]    (start, count) of the candidates each workgroup wrote, per pass parity
-    u32* swg;                // [2][batch][G][kSwgStride]  per-workgroup suffix sums of its local histogram, per pass parity
+    u32* ghist;              // [6][batch][kMaxBins]  global histograms: a ring of four for the passes, the sample's, the prefilter's second
+    u32* seg;                // [2][batch][G][2]    (start, count) of the candidates each workgroup wrote, per candidate array
+    u32* swg;                // [4][batch][G][kSwgStride]  per-workgroup suffix sums of its local histogram: a ring of three, the prefilter's second
     uint2* cand[2];          // [batch][n]          (raw bits, index) candidates, ping-pong
     unsigned long long* dbg; // [batch][G][16]      optional per-workgroup timestamps (diagnostic builds only)
     long long n, k;

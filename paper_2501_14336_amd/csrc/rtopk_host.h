@@ -25,6 +25,8 @@ rtopk_status launch_f16(const Params& P, const Config& c, bool scaled, hipStream
 rtopk_status launch_bf16(const Params& P, const Config& c, bool scaled, hipStream_t st, void* const* events);
 
 // Launch geometry the host needs for sizing.
+constexpr int kHostHistBuffers = 6;  // global histograms per row: four in rotation, the sample's, the prefilter's second
+constexpr int kHostSwgBuffers = 4;   // per-workgroup record sets per row: three in rotation, the prefilter's second
 constexpr int kHostGridBlock = 512;
 constexpr int kHostElemsPerLane = 16;
 

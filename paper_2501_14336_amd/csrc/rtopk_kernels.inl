@@ -73,6 +73,7 @@ template <int B, int ST = kStage>
 struct Shared {
     static constexpr int kStageEntries = ST;
     u32 hist[kMaxBins];
+    u32 hist2[kMaxBins];               // the prefilter sweep's second histogram: next digit of what it keeps in its bound's bin
     u32 wsum[B / 64];
     u32 red[2 * (B / 64)];
     u32 selv[5];                      // selectBin's result: bin, count above it, count inside it; distrust flag; total
@@ -96,7 +97,11 @@ struct PassEntry {
     bool finished;   // an earlier pass completed the row
     bool prev_multi; // the previous pass was run by the many-workgroup kernels
     bool in_lds;     // the candidates are in the workgroup's LDS list (few of them), not in the candidate array
+    u32 src_array;   // which of the two candidate arrays holds them (meaningless for pass 0 over X)
 };
+// Which candidate array a pass wrote is part of its record (bit 24 of `window`): a pass that reads array a writes
+// array 1 - a, a pass over X writes array 0, the prefilter sweep writes array 1.
+constexpr u32 kWindowArrayBit = 24;
 
 // Few enough candidates are ranked directly against each other (one per lane) instead of walking the
 // remaining digits; the list lives where the LDS histogram is, which no longer has a use then.
@@ -112,6 +117,7 @@ __device__ __forceinline__ PassEntry pass_entry(const Params& P, const rtopk_row
         e.finished = false;
         e.prev_multi = true;
         e.in_lds = false;
+        e.src_array = 1;  // (what a prefilter sweep kept)
     } else {
         e.cand = st->pass_rec[p - 1].cand_after;
         e.k_rem = st->pass_rec[p - 1].k_after;
@@ -119,6 +125,7 @@ __device__ __forceinline__ PassEntry pass_entry(const Params& P, const rtopk_row
         e.finished = e.cand == 0;
         e.prev_multi = st->pass_rec[p - 1].where == 1u;
         e.in_lds = false;
+        e.src_array = (st->pass_rec[p - 1].window >> kWindowArrayBit) & 1u;
     }
     return e;
 }
@@ -212,13 +219,30 @@ struct PlainCounts {
     __device__ __forceinline__ u32 operator()(u32 j, bool*) const { return c[j]; }
 };
 
-// The row's global histogram for pass p (three buffers in rotation: read p % 3, fill (p + 1) % 3, clear the third).
-__device__ __forceinline__ u32* global_hist(const Params& P, int p, int row) {
-    return P.ghist + ((size_t)(p % 3) * P.batch + row) * kMaxBins;
+// The row's global histogram for pass p.  Four buffers in rotation: pass p reads p % 4, fills (p + 1) % 4 with the
+// next digit's counts and clears (p + 2) % 4, which the pass after it fills (a buffer is never cleared by the launch
+// that reads it: the pass that stands for two digits reads two of them).  A fifth buffer holds the histogram of the
+// row's sample before a prefilter sweep.
+// And a sixth the prefilter sweep's second histogram (the digit after its own, of what it kept in its bound's bin),
+// which is read only if pass 0 finds that bin to be the k-th key's.
+constexpr int kHistRing = 4, kHistSample = 4, kHistSecond = 5, kSwgRing = 3, kSwgSecond = 3;
+__device__ __forceinline__ u32* hist_buffer(const Params& P, int which, int row) {
+    return P.ghist + ((size_t)which * P.batch + row) * kMaxBins;
+}
+__device__ __forceinline__ u32* global_hist(const Params& P, int p, int row) { return hist_buffer(P, p % kHistRing, row); }
+// Per-workgroup suffix sums of pass p's digit (three buffers in rotation, for the same reason; a fourth for the
+// prefilter sweep's second histogram).
+__device__ __forceinline__ u32* swg_buffer(const Params& P, int which, int row) {
+    return P.swg + ((size_t)which * P.batch + row) * P.G * kSwgStride;
+}
+__device__ __forceinline__ u32* swg_records(const Params& P, int p, int row) { return swg_buffer(P, p % kSwgRing, row); }
+// (start, count) of the candidates each workgroup wrote into candidate array a.
+__device__ __forceinline__ u32* seg_records(const Params& P, u32 a, int row) {
+    return P.seg + ((size_t)a * P.batch + row) * P.G * 2;
 }
 
 __device__ __forceinline__ void write_pass_record(rtopk_row_trace* st, int p, const PassInfo pi, const PassEntry& e,
-                                                  const Selection& sel, u32 where) {
+                                                  const Selection& sel, u32 where, u32 out_array) {
     // one thread; every field is written exactly once per call
     st->pass_rec[p].bin = sel.bin;
     st->pass_rec[p].k_after = sel.emit_all ? 0u : sel.k_inside;
@@ -226,7 +250,7 @@ __device__ __forceinline__ void write_pass_record(rtopk_row_trace* st, int p, co
     st->pass_rec[p].winners = sel.above + (sel.emit_all ? sel.inside : 0u);
     st->pass_rec[p].out_before = e.out_before;
     st->pass_rec[p].cand_before = e.cand;
-    st->pass_rec[p].window = pi.src | (pi.shift << 8) | (pi.bits << 16);
+    st->pass_rec[p].window = pi.src | (pi.shift << 8) | (pi.bits << 16) | (out_array << kWindowArrayBit);
     st->pass_rec[p].where = where;
 }
 
@@ -493,15 +517,15 @@ __device__ __forceinline__ Selection hist_phase(const Source& src, const Params&
     if (SINGLE) {
         return select_pass<B>([&](u32 j, bool*) __attribute__((always_inline)) { return copies_of(j); }, nb, e, sm, st);
     } else {
-        // (the sample's histogram stands before pass 0: buffer (0 - 1) mod 3; nobody needs its per-workgroup records)
-        u32* ghist = P.ghist + ((size_t)(P.pre_stride != 0 ? 2 : p % 3) * P.batch + row) * kMaxBins;
+        // (the sample's histogram has a buffer of its own; nobody needs its per-workgroup records)
+        u32* ghist = P.pre_stride != 0 ? hist_buffer(P, kHistSample, row) : global_hist(P, p, row);
         for (int j = tid; j < nb; j += B) {
             u32 c = sm.hist[j];
             if (c) atomicAdd(&ghist[j], c);
         }
         if (P.pre_stride != 0) return none;
         suffix_sums_in_place<B>(sm.hist, nb, sm.wsum);
-        u32* mine = P.swg + (((size_t)(p & 1) * P.batch + row) * P.G + wg) * kSwgStride;
+        u32* mine = swg_records(P, p, row) + (size_t)wg * kSwgStride;
         for (int j = tid; j < nb; j += B) mine[j] = sm.hist[j];
         if (tid == 0) mine[nb] = 0;
         return none;
@@ -527,9 +551,10 @@ struct ClassifyOut {
     uint2* cand_out;     // row's next candidate array
     uint2* cand_lds;     // or, when the candidates are few and one workgroup owns the row, the LDS list
     u32 kk, ncap;        // capacities (writes beyond them are dropped; they never happen in a consistent run)
-    // integer mode: an element wins iff (int)digit > bw (bin, or bin - 1 when the whole bin wins) and stays a
-    // candidate iff digit == b and it does not win
-    int bw;
+    // integer mode: an element wins iff wmin <= digit <= wmax and stays a candidate iff digit == b and it does not
+    // win.  An ordinary pass: wmin = b + 1 (b when the whole bin wins), wmax = the largest digit.  The digit may be
+    // a window of several passes' digits (see classify_phase, MERGED).
+    u32 wmin, wmax;
     u32 b;
     // float mode (first pass over X only): the same two tests as comparisons of the element itself with the
     // numbers whose keys are the bin's boundaries:  win = (x < t1) ^ flip,  at-least-candidate = (x < t2) ^ flip
@@ -587,7 +612,7 @@ __device__ __forceinline__ void slot_masks(const Source& src, const typename Sou
             mw = 0;
             mc = ballot64(d >= o.b) & vm;
         } else {
-            mw = ballot64((int)d > o.bw) & vm;
+            mw = ballot64(d >= o.wmin && d <= o.wmax) & vm;
             mc = ballot64(d == o.b) & vm & ~mw;
         }
     }
@@ -643,23 +668,28 @@ struct NextCount {
     PassInfo pi;
     u32 dirmask, idx_max;
     float a_s;
-    // the prefilter sweep that counts by raw bits (prefilter_tile_raw) leaves its NaN bookkeeping to the write-back:
-    bool nan_fix = false;   // move the count of every staged NaN from the raw bin of its bits to the NaNs' own bin
+    // The prefilter sweep (nothing of the following applies to any other pass):
+    // it counts its own digit for every element in the sweep, not here; what it does leave to the write-back is
+    bool nan_fix = false;   // (raw-bit counting, prefilter_tile_raw) move the count of every staged NaN from the raw
+                            // bin of its bits (digit shift nan_shift) to the NaNs' own bin nan_bin of `hist`
     bool discard = false;   // ... and write nothing (the prefilter declined: what is staged is staged for this only)
-    u32 nan_hist_shift = 0, nan_bin = 0;
+    bool count_if = false;  // count digit `pi` (the digit AFTER the sweep's own) into hist2, for the entries whose
+                            // key above that digit equals only_bin, i.e. that lie in the sweep's bound bin
+    HistSlot hist2{nullptr};
+    u32 only_bin = 0, nan_shift = 0, nan_bin = 0;
 };
-enum : u32 { kFlushToList = 1u, kFlushCount = 2u, kFlushNanFix = 4u, kFlushDiscard = 8u };
+enum : u32 { kFlushToList = 1u, kFlushCount = 2u, kFlushNanFix = 4u, kFlushDiscard = 8u, kFlushCountIf = 16u };
 
 // what (kFlush* bits): to-list -- the candidates go to the LDS list cand_lds instead of cand_out; count -- the next
 // pass's digit, described by (src, shift, bits, dirmask, idx_max, a_s), is counted into the LDS histogram hist;
-// NaN-fix -- hist is the CURRENT pass's raw-bit histogram (prefilter_tile_raw), shift its digit's shift and idx_max
-// the bin all NaNs share: every staged NaN's count is moved there; discard -- nothing is written.
+// the other three are the prefilter sweep's (see NextCount).
 // (Flags, not null tests: an LDS pointer to the start of the workgroup's LDS is the number 0, and a null generic
 // pointer casts to -1.)
 template <int DT>
 __device__ __forceinline__ void flush_candidates_body(uint2* cand_out, Lds<u64>* cand_lds, u32 ncap, Lds<u64>* buf,
-                                                      Lds<u32>* run, u32 fill, u32 lane, Lds<u32>* hist, u32 src, u32 shift,
-                                                      u32 bits, u32 dirmask, u32 idx_max, float a_s, u32 what) {
+                                                      Lds<u32>* run, u32 fill, u32 lane, Lds<u32>* hist, Lds<u32>* hist2,
+                                                      u32 src, u32 shift, u32 bits, u32 dirmask, u32 idx_max, float a_s,
+                                                      u32 what, u32 only_bin, u32 nan_shift, u32 nan_bin) {
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     u32 base = 0;
     if (!(what & kFlushDiscard)) {
@@ -676,21 +706,33 @@ __device__ __forceinline__ void flush_candidates_body(uint2* cand_out, Lds<u64>*
         } else if (pos < ncap) {
             ((Glb<u64>*)cand_out)[pos] = e;
         }
-        if (what & kFlushCount) {
-            // as hist_add: the lanes that hold the first active lane's digit share one LDS atomic
-            const u32 dg = digit_of<DT, SRC_RUNTIME>(pi, (u32)e, (u32)(e >> 32), dirmask, idx_max, a_s);
-            const u32 d0 = __builtin_amdgcn_readfirstlane(dg);
-            const bool same = dg == d0;
-            const u64 m = ballot64(same);
-            const bool leader = lane == (u32)__builtin_ctzll(m);
-            if (!same || leader)
-                __hip_atomic_fetch_add(hist + dg, same ? (u32)__popcll(m) : 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        if (what & (kFlushCount | kFlushCountIf)) {
+            u32 dg;
+            Lds<u32>* h = hist;
+            bool mine = true;
+            if (what & kFlushCountIf) {
+                const u32 key = KeyOf<DT>::key((u32)e) ^ dirmask;
+                mine = (key >> (shift + bits)) == only_bin;
+                dg = (key >> shift) & ((1u << bits) - 1u);
+                h = hist2;
+            } else {
+                dg = digit_of<DT, SRC_RUNTIME>(pi, (u32)e, (u32)(e >> 32), dirmask, idx_max, a_s);
+            }
+            if (mine) {
+                // as hist_add: the lanes that hold the first active lane's digit share one LDS atomic
+                const u32 d0 = __builtin_amdgcn_readfirstlane(dg);
+                const bool same = dg == d0;
+                const u64 m = ballot64(same);
+                const bool leader = lane == (u32)__builtin_ctzll(m);
+                if (!same || leader)
+                    __hip_atomic_fetch_add(h + dg, same ? (u32)__popcll(m) : 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            }
         }
         if (DT == RTOPK_F32 && (what & kFlushNanFix)) {
             const u32 raw = (u32)e;
             if ((raw & 0x7fffffffu) > 0x7f800000u) {
-                __hip_atomic_fetch_add(hist + (raw >> shift), ~0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                __hip_atomic_fetch_add(hist + idx_max, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                __hip_atomic_fetch_add(hist + (raw >> nan_shift), ~0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                __hip_atomic_fetch_add(hist + nan_bin, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
             }
         }
     }
@@ -698,10 +740,11 @@ __device__ __forceinline__ void flush_candidates_body(uint2* cand_out, Lds<u64>*
 }
 template <int DT>
 __device__ __noinline__ void flush_wave_candidates(uint2* cand_out, Lds<u64>* cand_lds, u32 ncap, Lds<u64>* buf,
-                                                   Lds<u32>* run, u32 fill, u32 lane, Lds<u32>* hist, u32 src, u32 shift,
-                                                   u32 bits, u32 dirmask, u32 idx_max, float a_s, u32 what) {
-    flush_candidates_body<DT>(cand_out, cand_lds, ncap, buf, run, fill, lane, hist, src, shift, bits, dirmask, idx_max, a_s,
-                              what);
+                                                   Lds<u32>* run, u32 fill, u32 lane, Lds<u32>* hist, Lds<u32>* hist2,
+                                                   u32 src, u32 shift, u32 bits, u32 dirmask, u32 idx_max, float a_s,
+                                                   u32 what, u32 only_bin, u32 nan_shift, u32 nan_bin) {
+    flush_candidates_body<DT>(cand_out, cand_lds, ncap, buf, run, fill, lane, hist, hist2, src, shift, bits, dirmask, idx_max,
+                              a_s, what, only_bin, nan_shift, nan_bin);
 }
 
 // INLINE: the write-back is expanded in place.  A call costs more than its instructions: a function starts by
@@ -719,16 +762,17 @@ __device__ __forceinline__ void flush_winners(const ClassifyOut<DT>& o, const ui
 template <int DT, bool INLINE = false>
 __device__ __forceinline__ void flush_candidates(const ClassifyOut<DT>& o, const uint2* buf, u32* run, u32 fill, u32 lane,
                                                  const NextCount& nc) {
-    const u32 what = (o.cand_lds != nullptr ? kFlushToList : 0u) | (nc.hist.h != nullptr && !nc.nan_fix ? kFlushCount : 0u) |
-                     (nc.nan_fix ? kFlushNanFix : 0u) | (nc.discard ? kFlushDiscard : 0u);
-    const u32 shift = nc.nan_fix ? nc.nan_hist_shift : nc.pi.shift;
-    const u32 imax = nc.nan_fix ? nc.nan_bin : nc.idx_max;
+    const bool pre = nc.nan_fix || nc.count_if || nc.discard;
+    const u32 what = (o.cand_lds != nullptr ? kFlushToList : 0u) | (nc.hist.h != nullptr && !pre ? kFlushCount : 0u) |
+                     (nc.nan_fix ? kFlushNanFix : 0u) | (nc.discard ? kFlushDiscard : 0u) | (nc.count_if ? kFlushCountIf : 0u);
     if constexpr (INLINE)
         flush_candidates_body<DT>(o.cand_out, lds_words(o.cand_lds), o.ncap, lds_words(buf), lds_word(run), fill, lane,
-                                  lds_word(nc.hist.h), nc.pi.src, shift, nc.pi.bits, nc.dirmask, imax, nc.a_s, what);
+                                  lds_word(nc.hist.h), lds_word(nc.hist2.h), nc.pi.src, nc.pi.shift, nc.pi.bits, nc.dirmask,
+                                  nc.idx_max, nc.a_s, what, nc.only_bin, nc.nan_shift, nc.nan_bin);
     else
         flush_wave_candidates<DT>(o.cand_out, lds_words(o.cand_lds), o.ncap, lds_words(buf), lds_word(run), fill, lane,
-                                  lds_word(nc.hist.h), nc.pi.src, shift, nc.pi.bits, nc.dirmask, imax, nc.a_s, what);
+                                  lds_word(nc.hist.h), lds_word(nc.hist2.h), nc.pi.src, nc.pi.shift, nc.pi.bits, nc.dirmask,
+                                  nc.idx_max, nc.a_s, what, nc.only_bin, nc.nan_shift, nc.nan_bin);
 }
 
 // Entries waiting in this wave's staging area (wave-uniform): winners in [0, fillW), candidates in
@@ -839,6 +883,12 @@ __device__ __forceinline__ void prefilter_tile_raw(const Source& src, const type
 // Where the histogram of a pass is.
 enum { HIST_IN_LDS = 0, HIST_IN_GLOBAL = 1 };
 
+// Are the digits of passes p and p + 1 adjacent windows of the ordered key itself, so that both can be read as one digit?
+__device__ __forceinline__ bool pass_pair_is_one_window(const Params& P, int p) {
+    return p + 1 < P.npass && P.pass[p].src == SRC_KEY && P.pass[p + 1].src == SRC_KEY &&
+           P.pass[p + 1].shift + P.pass[p + 1].bits == P.pass[p].shift;
+}
+
 // `sel` is selectBin's decision for this pass, made by select_pass (which also prepared the LDS histogram and
 // the running write positions).  SINGLE: the row is handled by this workgroup alone (wg = 0, G = 1);
 // otherwise G workgroups share the row.
@@ -848,15 +898,21 @@ enum { HIST_IN_LDS = 0, HIST_IN_GLOBAL = 1 };
 // of a bin >= sel.bin goes to the candidate array (into a segment of fixed position: there are no counts yet to
 // derive exact offsets from), and this same first digit is counted for EVERY element of X, kept or not (the
 // exact histogram pass 0 selects on, and the per-workgroup records either kind of pass 0 takes its offsets from).
+// sel0 (many workgroups, pass 1 on what a prefilter sweep kept, only): pass 0 had no sweep of its own.  The prefilter
+// sweep counted pass 1's digit for what it kept in its bound's bin; when the exact counts make that bin the k-th
+// key's bin (sel0->bin), `sel` is pass 1's selectBin on those counts, and this one sweep stands for both passes: it
+// classifies by the two digits taken as one (better than bin 0's digit, or in it and better than bin 1's: a winner).
 template <class Source, int DT, int SRC, int B, bool SINGLE, class Resident = NoResident, bool PRE = false, int ST = kStage>
 __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Params& P, int p, int row, u32 wg, u32 G,
                                                     const PassEntry& e, rtopk_row_trace* st, float a_s, Shared<B, ST>& sm,
                                                     u32 where, const Selection& sel, u32 records, bool own_segment,
-                                                    const Resident& resident = Resident()) {
+                                                    const Resident& resident = Resident(), const Selection* sel0 = nullptr) {
     constexpr bool kResident = !std::is_same<Resident, NoResident>::value;
     static_assert(!PRE || (!SINGLE && !kResident && SRC != SRC_RUNTIME), "the prefilter is a grid sweep over X");
-    const DigitCtx ctx = make_digit_ctx(P, p, a_s);
-    const int nb = 1 << ctx.pi.bits;
+    DigitCtx ctx = make_digit_ctx(P, p, a_s);
+    const PassInfo own_pi = ctx.pi;
+    if (sel0) ctx.pi.bits += P.pass[p - 1].bits;  // the digit window of both passes
+    const int nb = 1 << own_pi.bits;
     const u32 tid = threadIdx.x;
     const u32 lane = lane_id();
     const u32 wave = tid >> 6;
@@ -866,43 +922,52 @@ __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Par
     unsigned long long t_begin = wall_clock64(), t_pro = 0, t_sweep = 0;
 #endif
     u32 runW = e.out_before, runC = 0, myC = 0;
+    // which candidate array this pass writes: the other one than it reads; array 0 from X; a prefilter sweep array 1
+    const bool from_x = !std::is_same<Source, CandSource<B, kVecs>>::value;
+    const u32 out_array = PRE ? 1u : from_x ? 0u : 1u - e.src_array;
     if constexpr (PRE) {
         // this workgroup's segment starts where the tiles of the workgroups before it would end if every element
         // of theirs were kept (tiles are dealt round-robin: workgroup v has ntiles / G of them, one more if
         // v < ntiles % G)
         const u32 q = ntiles / G, r = ntiles % G;
         runC = (wg * q + (wg < r ? wg : r)) * (u32)(B * Source::kSlots);
-        if (wg == 0) {
-            u32* other = P.ghist + ((size_t)1 * P.batch + row) * kMaxBins;  // rotation with p = -1: read 2, fill 0, clear 1
-            for (int j = tid; j < kMaxBins; j += B) other[j] = 0;
-        }
     } else if (!SINGLE) {
         // exact write offsets: sum, at the chosen bin, the stored suffix sums of the workgroups before this one
         // (`records` workgroups have a record for this pass)
         const u32 upto = wg < records ? wg : records;
-        const u32* swg_row = P.swg + ((size_t)(p & 1) * P.batch + row) * P.G * kSwgStride;
+        const u32* swg_row = sel0 ? swg_buffer(P, kSwgSecond, row) : swg_records(P, p, row);
+        const u32* swg_row0 = sel0 ? swg_records(P, p - 1, row) : swg_row;
         u32 W = 0, C = 0;
         for (u32 w = tid; w < upto; w += B) {
             const u32* rec = swg_row + (size_t)w * kSwgStride;
             const u32 sb = rec[sel.bin], sb1 = rec[sel.bin + 1];
             W += sel.emit_all ? sb : sb1;
             C += sel.emit_all ? 0u : sb - sb1;
+            if (sel0) W += swg_row0[(size_t)w * kSwgStride + sel0->bin + 1];
         }
         block_sum2<B>(W, C, sm.red);
-        runW += W;
+        runW = (sel0 ? 0u : e.out_before) + W;
         runC = C;
         if (wg < records && !sel.emit_all) {
             const u32* rec = swg_row + (size_t)wg * kSwgStride;
             myC = rec[sel.bin] - rec[sel.bin + 1];
         }
         if (wg == 0) {
-            // histogram buffer (p + 2) % 3 was read by the previous pass and is filled by the next one: clear it
-            u32* other = P.ghist + ((size_t)((p + 2) % 3) * P.batch + row) * kMaxBins;
+            // the histogram buffer two ahead in the ring is filled by the next pass: clear it (its last reader was
+            // an earlier launch)
+            u32* other = global_hist(P, p + 2, row);
             for (int j = tid; j < kMaxBins; j += B) other[j] = 0;
         }
     }
     if (!PRE && wg == 0 && tid == 0) {
-        write_pass_record(st, p, ctx.pi, e, sel, where);
+        if (sel0) {
+            // pass 0's record: what its selectBin decided; its winners leave in this sweep
+            const PassEntry e0 = pass_entry(P, st, 0);
+            write_pass_record(st, 0, P.pass[0], e0, *sel0, where, e.src_array);
+            st->pass_rec[0].cand_before = st->pre_kept;
+            st->pre_merged = 1u;
+        }
+        write_pass_record(st, p, own_pi, e, sel, where, out_array);
         // after a prefilter the first digit pass looks at what the prefilter kept, not at all of X
         if (!SINGLE && SRC == SRC_RUNTIME && p == 0) st->pass_rec[0].cand_before = st->pre_kept;  // after a prefilter
     }
@@ -922,12 +987,15 @@ __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Par
     ClassifyOut<DT> o;
     o.out_v = (char*)P.out_values + (size_t)row * (size_t)P.k * KeyOf<DT>::kBytes;
     o.out_i = P.out_indices + (size_t)row * (size_t)P.k;
-    o.cand_out = P.cand[(pn - 1) & 1] + (size_t)row * P.cand_stride;
+    o.cand_out = P.cand[out_array] + (size_t)row * P.cand_stride;
     o.cand_lds = to_rank ? (uint2*)sm.hist : nullptr;
     o.kk = (u32)P.k;
     o.ncap = (u32)P.cand_stride;
-    o.b = sel.bin;
-    o.bw = sel.emit_all ? (int)sel.bin - 1 : (int)sel.bin;
+    // (with sel0: the window holds pass p - 1's digit above pass p's own)
+    o.b = sel0 ? (sel0->bin << own_pi.bits) | sel.bin : sel.bin;
+    o.wmax = ctx.pi.bits >= 32u ? 0xffffffffu : (1u << ctx.pi.bits) - 1u;
+    o.wmin = sel.emit_all ? o.b : o.b + 1u;
+    if (!sel.emit_all && o.b == o.wmax) { o.wmin = 1u; o.wmax = 0u; }  // the top bin: nothing lies above it
     // First pass over X: the digit is the key's top bits, so "digit > b" and "digit >= b" are comparisons of
     // the element with two numbers -- two instructions per element instead of the whole key transform.
     bool floatcmp = false;
@@ -970,6 +1038,13 @@ __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Par
         }
     }
 
+    bool count_second = false;
+    if constexpr (PRE) {
+        count_second = pass_pair_is_one_window(P, p) && sel.bin < (1u << ctx.pi.bits);
+        if (count_second)
+            for (int j = tid; j < kMaxBins; j += B) sm.hist2[j] = 0;
+    }
+
     if (!SINGLE) {
         if (tid == 0) {
             sm.runW = runW;
@@ -989,11 +1064,19 @@ __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Par
     nc.dirmask = ctx.dirmask;
     nc.idx_max = ctx.idx_max;
     nc.a_s = ctx.a_s;
+    // The prefilter sweep counts pass p + 1's digit of what it keeps in its bound's bin, so that pass p needs no
+    // sweep of its own when that bin turns out to be the k-th key's (see sel0).
+    if (count_second) {
+        nc.count_if = true;
+        nc.hist2 = HistSlot{sm.hist2};
+        nc.pi = P.pass[p + 1];
+        nc.only_bin = sel.bin;
+    }
     if (raw_pre) {
         nc.hist = HistSlot{sm.hist};
         nc.nan_fix = true;
         nc.discard = keep_none;
-        nc.nan_hist_shift = ctx.pi.shift;
+        nc.nan_shift = ctx.pi.shift;
         nc.nan_bin = (1u << (ctx.pi.bits - 1u)) - 1u;
     }
     if constexpr (kResident && SRC != SRC_RUNTIME) {
@@ -1080,7 +1163,7 @@ __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Par
             __syncthreads();
         }
         if (!SINGLE) {
-            u32* gnext = P.ghist + ((size_t)(pn % 3) * P.batch + row) * kMaxBins;
+            u32* gnext = global_hist(P, pn, row);
             for (int j = tid; j < nb_next; j += B) {
                 const u32 c = sm.hist[j];
                 if (c) atomicAdd(&gnext[j], c);
@@ -1088,15 +1171,28 @@ __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Par
         }
         if (next_multi) suffix_sums_in_place<B>(sm.hist, nb_next, sm.wsum);
         if (next_multi) {
-            u32* mine = P.swg + (((size_t)(pn & 1) * P.batch + row) * P.G + wg) * kSwgStride;
+            u32* mine = swg_records(P, pn, row) + (size_t)wg * kSwgStride;
             for (int j = tid; j < nb_next; j += B) mine[j] = sm.hist[j];
             if (tid == 0) {
                 mine[nb_next] = 0;
-                u32* seg = P.seg + (((size_t)((pn - 1) & 1) * P.batch + row) * P.G + wg) * 2;
+                u32* seg = seg_records(P, out_array, row) + (size_t)wg * 2;
                 seg[0] = runC;
                 seg[1] = PRE ? sm.runC - runC : myC;  // (the prefilter learns its count by writing)
                 if (PRE) atomicAdd(&st->pre_kept, sm.runC - runC);
             }
+        }
+        if (count_second) {
+            // the second histogram of a prefilter sweep, published like the first, in buffers of its own
+            const int nb2 = 1 << P.pass[pn + 1].bits;
+            u32* g2 = hist_buffer(P, kHistSecond, row);
+            for (int j = tid; j < nb2; j += B) {
+                const u32 c = sm.hist2[j];
+                if (c) atomicAdd(&g2[j], c);
+            }
+            suffix_sums_in_place<B>(sm.hist2, nb2, sm.wsum);
+            u32* mine2 = swg_buffer(P, kSwgSecond, row) + (size_t)wg * kSwgStride;
+            for (int j = tid; j < nb2; j += B) mine2[j] = sm.hist2[j];
+            if (tid == 0) mine2[nb2] = 0;
         }
     }
 #ifdef RTOPK_TIMING
@@ -1114,6 +1210,7 @@ __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Par
     next.finished = sel.emit_all;
     next.prev_multi = !SINGLE;
     next.in_lds = to_rank;
+    next.src_array = out_array;
     return next;
 }
 
@@ -1148,7 +1245,7 @@ __device__ __forceinline__ float init_row(const Params& P, int row, rtopk_row_tr
 template <int DT>
 __global__ void __launch_bounds__(256) k_init(Params P) {
     const int row = blockIdx.x;
-    for (int h = 0; h < 3; ++h) {
+    for (int h = 0; h < kHostHistBuffers; ++h) {
         u32* ghist = P.ghist + ((size_t)h * P.batch + row) * kMaxBins;
         for (int j = threadIdx.x; j < kMaxBins; j += 256) ghist[j] = 0;
     }
@@ -1217,7 +1314,7 @@ __global__ void __launch_bounds__(kGridBlock) k_prefilter_keys(Params P) {
     // a rank beyond the sample (or an empty sample) selects nothing: bin 0, everything is kept
     e.k_rem = sample.rank < (u64)sample.elems ? (u32)sample.rank : sample.elems + 1u;
     bool ignored;
-    Selection sel = select_pass<kGridBlock>(PlainCounts{global_hist(P, 2, row)}, 1 << P.pass[0].bits, e, sm, st, &ignored);
+    Selection sel = select_pass<kGridBlock>(PlainCounts{hist_buffer(P, kHistSample, row)}, 1 << P.pass[0].bits, e, sm, st, &ignored);
     // If the sample says that more than an eighth of the row (a sixteenth for 16-bit keys, whose candidates are
     // four times their size) lies in the bins that would be kept -- keys crowded into one bin: a narrow range,
     // many duplicates --, writing that much out and reading it back costs more than the second sweep over X:
@@ -1241,14 +1338,34 @@ __global__ void __launch_bounds__(kGridBlock) k_pass0_after_prefilter(Params P) 
     rtopk_row_trace* st = row_state(P, row);
     const PassEntry e = pass_entry(P, st, 0);
     const Selection sel = select_pass<kGridBlock>(PlainCounts{global_hist(P, 0, row)}, 1 << P.pass[0].bits, e, sm, st);
-    if (sel.bin >= st->pre_bound) {
-        const u32* seg = P.seg + (((size_t)1 * P.batch + row) * P.G + blockIdx.x) * 2;
+    const u32 bound = st->pre_bound;
+    if (sel.bin >= bound) {
+        const u32* seg = seg_records(P, 1u, row) + (size_t)blockIdx.x * 2;
         CandSource<kGridBlock, kVecs> src;
         src.init(P.cand[1] + (size_t)row * P.cand_stride, seg[0], seg[1], (u32)P.cand_stride);
-        classify_phase<decltype(src), DT, SRC_RUNTIME, kGridBlock, false>(src, P, 0, row, blockIdx.x, gridDim.x, e, st,
-                                                                          st->a_s, sm, 1u, sel, gridDim.x, true);
+        if (sel.bin == bound && !sel.emit_all && pass_pair_is_one_window(P, 0)) {
+            // The bound's bin is the k-th key's: the sweep has counted pass 1's digit for exactly this bin, so pass 0
+            // is its selectBin and nothing else, and pass 1's sweep over what was kept classifies by both digits.
+            PassEntry e1;
+            e1.cand = sel.inside;
+            e1.k_rem = sel.k_inside;
+            e1.out_before = sel.above;
+            e1.finished = false;
+            e1.prev_multi = true;
+            e1.in_lds = false;
+            e1.src_array = 1u;
+            __syncthreads();  // everybody has read the first selectBin's result: its LDS words may be reused
+            const Selection sel1 = select_pass<kGridBlock>(PlainCounts{hist_buffer(P, kHistSecond, row)}, 1 << P.pass[1].bits,
+                                                           e1, sm, st);
+            classify_phase<decltype(src), DT, SRC_RUNTIME, kGridBlock, false>(src, P, 1, row, blockIdx.x, gridDim.x, e1, st,
+                                                                              st->a_s, sm, 1u, sel1, gridDim.x, true,
+                                                                              NoResident(), &sel);
+        } else {
+            classify_phase<decltype(src), DT, SRC_RUNTIME, kGridBlock, false>(src, P, 0, row, blockIdx.x, gridDim.x, e, st,
+                                                                              st->a_s, sm, 1u, sel, gridDim.x, true);
+        }
     } else {
-        if (blockIdx.x == 0 && threadIdx.x == 0) st->pre_missed = st->pre_bound == (1u << P.pass[0].bits) ? 2u : 1u;
+        if (blockIdx.x == 0 && threadIdx.x == 0) st->pre_missed = bound == (1u << P.pass[0].bits) ? 2u : 1u;
         KeySource<DT, kGridBlock, key_vecs<DT>(), NT> src;
         src.init(P.keys, P.n, row);
         const u32 ntiles = src.ntiles();
@@ -1263,11 +1380,14 @@ __global__ void __launch_bounds__(kGridBlock) k_classify_cand(Params P, int p) {
     __shared__ Shared<kGridBlock> sm;
     const int row = blockIdx.y;
     rtopk_row_trace* st = row_state(P, row);
+    // (pass 1 may have been done together with pass 0, by the launch before this one: st->pre_merged, which that
+    // launch wrote and this one only reads)
+    if (p == 1 && st->pre_merged != 0u) return;
     const PassEntry e = pass_entry(P, st, p);
     if (!multi_runs_pass(P, e, p)) return;
-    const u32* seg = P.seg + (((size_t)((p - 1) & 1) * P.batch + row) * P.G + blockIdx.x) * 2;
+    const u32* seg = seg_records(P, e.src_array, row) + (size_t)blockIdx.x * 2;
     CandSource<kGridBlock, kVecs> src;
-    src.init(P.cand[(p - 1) & 1] + (size_t)row * P.cand_stride, seg[0], seg[1], (u32)P.cand_stride);
+    src.init(P.cand[e.src_array] + (size_t)row * P.cand_stride, seg[0], seg[1], (u32)P.cand_stride);
     // its own tiles only: the segment is this workgroup's alone
     const Selection sel = select_pass<kGridBlock>(PlainCounts{global_hist(P, p, row)}, 1 << P.pass[p].bits, e, sm, st);
     classify_phase<decltype(src), DT, SRC_RUNTIME, kGridBlock, false>(src, P, p, row, blockIdx.x, gridDim.x, e, st, st->a_s,
@@ -1292,7 +1412,7 @@ __device__ __forceinline__ void rank_finish(const Params& P, int row, rtopk_row_
     uint2* list = (uint2*)sm.hist;                    // (raw bits, index)
     u64* ext = (u64*)(sm.hist + 2 * kRankCap);        // extended keys
     if (!e.in_lds) {
-        const uint2* cand = P.cand[(p - 1) & 1] + (size_t)row * P.cand_stride;
+        const uint2* cand = P.cand[e.src_array] + (size_t)row * P.cand_stride;
         if (tid < C) list[tid] = cand[tid];
     }
     __syncthreads();
@@ -1350,7 +1470,7 @@ __device__ __forceinline__ void finish_row(const Params& P, int row, rtopk_row_t
             return;
         }
         CandSource<kRowBlock, kVecs> src;
-        src.init(P.cand[(p - 1) & 1] + (size_t)row * P.cand_stride, 0u, e.cand, (u32)P.cand_stride);
+        src.init(P.cand[e.src_array] + (size_t)row * P.cand_stride, 0u, e.cand, (u32)P.cand_stride);
         const int nb = 1 << P.pass[p].bits;
         const Selection sel = hist_from == HIST_IN_GLOBAL
             ? select_pass<kRowBlock>(PlainCounts{global_hist(P, p, row)}, nb, e, sm, st)
@@ -1741,7 +1861,7 @@ __global__ void __launch_bounds__(kStreamBlock) __attribute__((amdgpu_waves_per_
         }
     }
     const PassEntry e0 = pass_entry(P, st, 0);
-    if (tid == 0) write_pass_record(st, 0, ctx.pi, e0, sel, 4u);
+    if (tid == 0) write_pass_record(st, 0, ctx.pi, e0, sel, 4u, 0u);
     if (sel.emit_all) return;
     __syncthreads();
     // ---- the ranking step (see rank_finish): C candidates, up to two per lane

@@ -56,7 +56,7 @@ def test_workspace_bytes_scales_with_the_candidate_arrays():
     # a forced workgroup count changes only the small per-workgroup records
     a = B.rtopk_workspace_bytes(1, 1 << 24, 5, 0, tuning=dict(path=2, wgs_per_row=64))
     b = B.rtopk_workspace_bytes(1, 1 << 24, 5, 0, tuning=dict(path=2, wgs_per_row=512))
-    assert 0 < b - a < (16 << 20)
+    assert 0 < b - a < (32 << 20)
 
 
 @pytest.mark.parametrize("args", [

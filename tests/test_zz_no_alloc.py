@@ -50,7 +50,7 @@ def test_static_scratch_matches_the_workspace_entry_point_twice_in_a_row():
     pairs = [
         (lambda n: W.llm_logits(24, n, 91), BF16, (131072, 40001), 50, True, 0),
         (lambda n: W.normal(2 * n, 92).view(np.uint32).reshape(2, n), F32, (300001, 70001), 256, False, 0),
-        (lambda n: W.normal(n, 93).view(np.uint32), F32, (3000001, 500001), 4096, True, 0),
+        (lambda n: W.normal(n, 93).view(np.uint32), F32, (2500001, 500001), 4096, True, 0),
         (lambda n: W.duplicates(n, 94).view(np.uint32), F32, (2000003, 300001), 150000, True, 0),
         (lambda n: W.uniform_range(n, 95, 128.6, 128.7).view(np.uint32), F32, (1 << 21, 1 << 19), 512, True, 1),
         (lambda n: W.normal(3 * n, 96).astype(np.float16).view(np.uint16).reshape(3, n), F16, (400001, 8195), 1000, False, 0),
