@@ -21,6 +21,7 @@
  * The selected SET is unique and reproducible.  The order of the k outputs
  * inside a row is unspecified (the paper's output is unsorted, Section 2.3.1);
  * the order may differ between runs with the same arguments (the set never does).
+ * With RTOPK_FLAG_SORTED the order is fixed too: best first, lowest index first among equals.
  */
 #ifndef RTOPK_H
 #define RTOPK_H
@@ -53,7 +54,13 @@ enum {
     RTOPK_FLAG_SCALING = 1u << 0,
     /* Accepted and without effect: the per-pass records (rtopk_row_trace below) are the library's own
      * loop state, so they are written on every call. */
-    RTOPK_FLAG_DEBUG_COUNTERS = 1u << 1
+    RTOPK_FLAG_DEBUG_COUNTERS = 1u << 1,
+    /* Sorted output: every row's k outputs in the order best element first (descending for "largest",
+     * ascending for "smallest"; NaN ranks above +inf, -0 below +0), lowest index first among equal elements.
+     * The paper's output is unsorted by nature (Section 2.3.1); its evaluation sorts afterwards and counts
+     * that time (Section 5.2).  Costs a sort of the k pairs after the selection: in LDS for k <= 8192, a
+     * radix sort in the workspace beyond. */
+    RTOPK_FLAG_SORTED = 1u << 2
 };
 
 /* Maximum row length: indices are kept in 32 bits inside the library. */

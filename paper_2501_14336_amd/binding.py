@@ -20,6 +20,7 @@ RTOPK_F32, RTOPK_F16, RTOPK_BF16 = 0, 1, 2
 RTOPK_OK = 0
 RTOPK_FLAG_SCALING = 1
 RTOPK_FLAG_DEBUG_COUNTERS = 2
+RTOPK_FLAG_SORTED = 4
 RTOPK_TRACE_STRIDE = 512
 RTOPK_TRACE_MAX_PASSES = 12
 
@@ -235,11 +236,11 @@ def _torch_dtype_code(t):
 
 
 def topk(x, k: int, largest: bool = True, scaling: bool = False, seed: int = 0, tuning=None, workspace=None,
-         out=None, events=None, check: bool = False):
+         out=None, events=None, check: bool = False, sorted: bool = False):
     """Top-k of every row of a CUDA/HIP tensor ``x`` ([n] or [batch, n]; fp32, fp16 or bf16).
 
     Returns (values [batch, k] of x.dtype, indices [batch, k] int64, workspace).  The order inside a row is
-    unspecified.  ``workspace`` (a uint8 tensor) and ``out`` (a (values, indices) pair) are reused if given.
+    unspecified unless ``sorted`` (then: best first, lowest index first among equals).  ``workspace`` (a uint8 tensor) and ``out`` (a (values, indices) pair) are reused if given.
     ``check``: synchronise and raise if a kernel flagged an inconsistent state in any row's record (the status
     of the call itself only covers arguments and launches).
     """
@@ -252,7 +253,7 @@ def topk(x, k: int, largest: bool = True, scaling: bool = False, seed: int = 0, 
         raise RtopkError(1, "input must be a contiguous [batch, n] tensor")
     batch, n = x.shape
     code = _torch_dtype_code(x)
-    flags = RTOPK_FLAG_SCALING if scaling else 0
+    flags = (RTOPK_FLAG_SCALING if scaling else 0) | (RTOPK_FLAG_SORTED if sorted else 0)
     need = rtopk_workspace_bytes(batch, n, k, code, flags, tuning)
     if workspace is None or workspace.numel() < need:
         workspace = torch.empty(need, dtype=torch.uint8, device=x.device)

@@ -18,7 +18,7 @@ namespace rtopk {
 // host side
 // ------------------------------------------------------------------------------------------------
 struct Layout {
-    size_t state_off, dbg_off, ghist_off, seg_off, swg_off, cand0_off, cand1_off, cand_stride, total;
+    size_t state_off, dbg_off, ghist_off, seg_off, swg_off, sort_hist_off, sort_state_off, cand0_off, cand1_off, cand_stride, total;
 };
 
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -29,7 +29,7 @@ static rtopk_status make_config(int64_t batch, int64_t n, int64_t k, rtopk_dtype
                                 const rtopk_tuning* tn, Config* c) {
     if (batch < 1 || batch > 0x7fffffff || n < 1 || n > RTOPK_MAX_N || k < 1 || k > n) return RTOPK_ERR_INVALID_ARG;
     if (dt != RTOPK_F32 && dt != RTOPK_F16 && dt != RTOPK_BF16) return RTOPK_ERR_INVALID_ARG;
-    if (flags & ~(uint32_t)(RTOPK_FLAG_SCALING | RTOPK_FLAG_DEBUG_COUNTERS)) return RTOPK_ERR_INVALID_ARG;
+    if (flags & ~(uint32_t)(RTOPK_FLAG_SCALING | RTOPK_FLAG_DEBUG_COUNTERS | RTOPK_FLAG_SORTED)) return RTOPK_ERR_INVALID_ARG;
     int d = dt == RTOPK_F32 ? 12 : 11;
     int path = 0, G = 0;
     u32 small = 65536;
@@ -97,6 +97,15 @@ static rtopk_status make_config(int64_t batch, int64_t n, int64_t k, rtopk_dtype
     } else {
         G = 1;
     }
+    // sorted output of rows too long for one workgroup's LDS: a radix sort on the grid, chunks of at least 8192 keys
+    c->Gs = 0;
+    if ((flags & RTOPK_FLAG_SORTED) && k > kHostSortSmall) {
+        int64_t want = 512 / batch, by_k = (k + 8191) / 8192;
+        if (want < 1) want = 1;
+        if (want > by_k) want = by_k;
+        c->Gs = (int)want;
+        if (batch > 65535) return RTOPK_ERR_INVALID_ARG;  // rows are the grid's y dimension there
+    }
     c->d = d;
     c->path = path;
     c->one_sweep = one_sweep;
@@ -159,6 +168,10 @@ static Layout make_layout(int64_t batch, int64_t n, const Config& c) {
     off = align_up(off + (size_t)2 * shared_rows * c.G * 2 * 4, 256);
     L.swg_off = off;
     off = align_up(off + (size_t)kHostSwgBuffers * shared_rows * c.G * kSwgStride * 4, 256);
+    L.sort_hist_off = off;
+    off = align_up(off + (size_t)batch * 256 * c.Gs * 4, 256);
+    L.sort_state_off = off;
+    off = align_up(off + (c.Gs ? (size_t)batch * 128 : 0), 256);
     // (the prefilter's per-workgroup segments are laid out by whole tiles: up to two tiles beyond n)
     L.cand_stride = (size_t)n + (c.prefilter ? (size_t)2 * kHostGridBlock * kHostElemsPerLane : 0);
     L.cand0_off = off;
@@ -264,6 +277,9 @@ rtopk_status rtopk_select_events(const void* keys, int64_t batch, int64_t n, int
     P.seg = (u32*)(ws + L.seg_off);
     P.dbg = (unsigned long long*)(ws + L.dbg_off);
     P.swg = (u32*)(ws + L.swg_off);
+    P.sort_hist = (u32*)(ws + L.sort_hist_off);
+    P.sort_state = (void*)(ws + L.sort_state_off);
+    P.Gs = c.Gs;
     P.cand[0] = (uint2*)(ws + L.cand0_off);
     P.cand[1] = (uint2*)(ws + L.cand1_off);
     P.cand_stride = L.cand_stride;

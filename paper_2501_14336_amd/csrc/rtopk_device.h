@@ -36,8 +36,10 @@ struct Params {
     u32* swg;                // [4][batch][G][kSwgStride]  per-workgroup suffix sums of its local histogram: a ring of three, the prefilter's second
     uint2* cand[2];          // [batch][n]          (raw bits, index) candidates, ping-pong
     unsigned long long* dbg; // [batch][G][16]      optional per-workgroup timestamps (diagnostic builds only)
+    u32* sort_hist;          // [batch][256][Gs]    sorted output of long rows: per-chunk digit counts, then offsets
+    void* sort_state;        // [batch] records of 128 bytes: which array holds the keys, which passes are skipped
     long long n, k;
-    int batch, G;
+    int batch, G, Gs;
     u32 dirmask;             // 0 for "largest"; all key bits set for "smallest" (complements the key)
     u32 idx_max;             // 2^ceil(log2 n) - 1: the index digit source is idx_max - index
     u32 small;               // candidate count at or below which one workgroup finishes the row

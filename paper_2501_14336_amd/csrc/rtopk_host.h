@@ -9,6 +9,7 @@ namespace rtopk {
 
 struct Config {
     int d, path, G;
+    int Gs;          // sorted output of long rows: workgroups per row of the radix sort (0: not needed)
     u32 small;
     int npass;
     bool one_sweep;  // path 1: try the one-sweep kernel (small k) first
@@ -27,6 +28,7 @@ rtopk_status launch_bf16(const Params& P, const Config& c, bool scaled, hipStrea
 // Launch geometry the host needs for sizing.
 constexpr int kHostHistBuffers = 6;  // global histograms per row: four in rotation, the sample's, the prefilter's second
 constexpr int kHostSwgBuffers = 4;   // per-workgroup record sets per row: three in rotation, the prefilter's second
+constexpr int kHostSortSmall = 8192;  // sorted output: rows of up to this many outputs are sorted by one workgroup in LDS
 constexpr int kHostGridBlock = 512;
 constexpr int kHostElemsPerLane = 16;
 

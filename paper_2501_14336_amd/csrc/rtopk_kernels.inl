@@ -1917,6 +1917,8 @@ __global__ void __launch_bounds__(kStreamBlock) __attribute__((amdgpu_waves_per_
     RTOPK_STAMP(5);
 }
 
+#include "rtopk_sort.inl"
+
 static void mark(void* const* events, int i, hipStream_t st) {
     if (events && events[i]) (void)hipEventRecord((hipEvent_t)events[i], st);
 }
@@ -1948,6 +1950,7 @@ static rtopk_status launch_all(const Params& P, const Config& c, bool scaled, hi
             hipLaunchKernelGGL((k_row<DT, kScaledSrc>), dim3(batch), dim3(kRowBlock), 0, st, P, false);
         else
             hipLaunchKernelGGL((k_row<DT, SRC_KEY>), dim3(batch), dim3(kRowBlock), 0, st, P, one_sweep);
+        if (P.flags & RTOPK_FLAG_SORTED) launch_sort<DT>(P, st);
         mark(events, 4, st);
         return hipGetLastError() == hipSuccess ? RTOPK_OK : RTOPK_ERR_HIP;
     }
@@ -2003,6 +2006,7 @@ static rtopk_status launch_all(const Params& P, const Config& c, bool scaled, hi
         hipLaunchKernelGGL((k_classify_cand<DT>), grid, block, 0, st, P, p);
     }
     hipLaunchKernelGGL((k_finish<DT>), dim3(batch), dim3(kRowBlock), 0, st, P);
+    if (P.flags & RTOPK_FLAG_SORTED) launch_sort<DT>(P, st);
     mark(events, 4, st);
     return hipGetLastError() == hipSuccess ? RTOPK_OK : RTOPK_ERR_HIP;
 }

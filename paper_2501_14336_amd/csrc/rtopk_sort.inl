@@ -1,0 +1,247 @@
+// Sorted output (RTOPK_FLAG_SORTED): after the selection, the k (value, index) pairs of every row are put into
+// the order best element first, lowest index first among equal elements.  The paper's output is unsorted by
+// nature (Section 2.3.1) and its evaluation sorts it afterwards (Section 5.2); this is that step, on the GPU.
+//
+// Every pair becomes one 64-bit sort key: the complement of the element's ordered key (so that ascending order is
+// best first) above its index.  The keys of a row are distinct.
+//   k <= kSortSmall: one workgroup per row sorts the keys in LDS (bitonic network).
+//   larger k: least-significant-digit radix sort, 8 bits per pass, on the two candidate arrays of the workspace
+//   (idle once the selection is done): per pass a histogram per workgroup chunk, one scan of the (bin, chunk)
+//   table, and a stable scatter.  A pass whose digit is the same for all keys of the row (the zero low half of a
+//   16-bit key, index bits above log2 n) is skipped.
+// The sorted keys are unpacked into the outputs; values are gathered again from X by index, so they keep their
+// original bits (NaN payloads, zero signs).
+//
+// Included by rtopk_kernels.inl (inside namespace rtopk).
+
+constexpr int kSortSmall = kHostSortSmall;  // pairs one workgroup sorts in LDS
+constexpr int kSortBlock = 512;         // threads per workgroup, radix sort kernels
+constexpr int kSortBins = 256;
+constexpr int kSortPasses = 8;
+// per-row state of the radix sort, in the workspace: cur[j] = which candidate array holds the keys when pass j
+// starts (cur[kSortPasses]: when all are done), skip[j] = pass j moves nothing
+struct SortState {
+    u32 cur[kSortPasses + 1];
+    u32 skip[kSortPasses];
+    u32 pad[32 - 2 * kSortPasses - 1];
+};
+static_assert(sizeof(SortState) == 128, "sort state record");
+
+template <int DT>
+__device__ __forceinline__ u64 sort_key_of(u32 raw, u32 idx, u32 dirmask) {
+    const u32 okey = KeyOf<DT>::key(raw) ^ dirmask;
+    return ((u64)(~okey) << 32) | (u64)idx;
+}
+template <int DT>
+__device__ __forceinline__ u32 load_value(const void* v, size_t i) {
+    return DT == RTOPK_F32 ? ((const u32*)v)[i] : (u32)((const uint16_t*)v)[i];
+}
+
+// k <= kSortSmall: bitonic sort of one row's keys in LDS.
+template <int DT>
+__global__ void __launch_bounds__(kRowBlock) k_sort_small(Params P) {
+    __shared__ u64 buf[kSortSmall];
+    constexpr int B = kRowBlock;
+    const int row = blockIdx.x;
+    const u32 tid = threadIdx.x;
+    const u32 k = (u32)P.k;
+    char* out_v = (char*)P.out_values + (size_t)row * (size_t)P.k * KeyOf<DT>::kBytes;
+    long long* out_i = P.out_indices + (size_t)row * (size_t)P.k;
+    const char* x = (const char*)P.keys + (size_t)row * (size_t)P.n * KeyOf<DT>::kBytes;
+    u32 m = 64;
+    while (m < k) m <<= 1;
+    for (u32 i = tid; i < m; i += B)
+        buf[i] = i < k ? sort_key_of<DT>(load_value<DT>(out_v, i), (u32)out_i[i], P.dirmask) : ~0ull;  // padding sorts last
+    for (u32 size = 2; size <= m; size <<= 1) {
+        for (u32 stride = size >> 1; stride > 0; stride >>= 1) {
+            __syncthreads();
+            for (u32 t = tid; t < m / 2; t += B) {
+                const u32 i = 2 * t - (t & (stride - 1));
+                const u32 j = i + stride;
+                const bool up = (i & size) == 0;
+                const u64 a = buf[i], b = buf[j];
+                if ((a > b) == up) {
+                    buf[i] = b;
+                    buf[j] = a;
+                }
+            }
+        }
+    }
+    __syncthreads();
+    for (u32 i = tid; i < k; i += B) {
+        const u32 idx = (u32)buf[i];
+        out_i[i] = (long long)idx;
+        store_value<DT>(out_v, i, load_value<DT>(x, idx));
+    }
+}
+
+// ---- radix sort of long rows ----
+__device__ __forceinline__ SortState* sort_state(const Params& P, int row) { return (SortState*)P.sort_state + row; }
+__device__ __forceinline__ u64* sort_buffer(const Params& P, u32 which, int row) {
+    return (u64*)(P.cand[which] + (size_t)row * P.cand_stride);
+}
+// the chunk of workgroup w: [begin, end), a whole number of kSortBlock-element tiles but for the row's end
+__device__ __forceinline__ void sort_chunk(const Params& P, u32 w, u32& begin, u32& end) {
+    const u32 k = (u32)P.k;
+    u32 per = (k + (u32)P.Gs - 1u) / (u32)P.Gs;
+    per = (per + kSortBlock - 1u) / kSortBlock * kSortBlock;
+    const u64 b = (u64)w * per, e = b + per;
+    begin = b < k ? (u32)b : k;
+    end = e < k ? (u32)e : k;
+}
+
+// outputs -> keys in candidate array 0
+template <int DT>
+__global__ void __launch_bounds__(kSortBlock) k_sort_pack(Params P) {
+    const int row = blockIdx.y;
+    const char* out_v = (const char*)P.out_values + (size_t)row * (size_t)P.k * KeyOf<DT>::kBytes;
+    const long long* out_i = P.out_indices + (size_t)row * (size_t)P.k;
+    u64* dst = sort_buffer(P, 0u, row);
+    u32 begin, end;
+    sort_chunk(P, blockIdx.x, begin, end);
+    for (u32 i = begin + threadIdx.x; i < end; i += kSortBlock)
+        dst[i] = sort_key_of<DT>(load_value<DT>(out_v, i), (u32)out_i[i], P.dirmask);
+    if (blockIdx.x == 0 && threadIdx.x < sizeof(SortState) / 4) ((u32*)sort_state(P, row))[threadIdx.x] = 0;
+}
+
+// histogram of pass j's digit over each workgroup's chunk: table[bin][workgroup]
+template <int DT>
+__global__ void __launch_bounds__(kSortBlock) k_sort_hist(Params P, int j) {
+    __shared__ u32 h[kSortBins];
+    const int row = blockIdx.y;
+    const u64* src = sort_buffer(P, sort_state(P, row)->cur[j], row);
+    if (threadIdx.x < kSortBins) h[threadIdx.x] = 0;
+    __syncthreads();
+    u32 begin, end;
+    sort_chunk(P, blockIdx.x, begin, end);
+    for (u32 i = begin + threadIdx.x; i < end; i += kSortBlock) atomicAdd(&h[(u32)(src[i] >> (8 * j)) & 255u], 1u);
+    __syncthreads();
+    u32* table = P.sort_hist + (size_t)row * kSortBins * P.Gs;
+    if (threadIdx.x < kSortBins) table[(size_t)threadIdx.x * P.Gs + blockIdx.x] = h[threadIdx.x];
+}
+
+// exclusive scan of the table in (bin, workgroup) order: where each workgroup's elements of each bin go
+template <int DT>
+__global__ void __launch_bounds__(kRowBlock) k_sort_scan(Params P, int j) {
+    __shared__ u32 wsum[kRowBlock / 64];
+    __shared__ u32 carry, all_in_one;
+    const int row = blockIdx.x;
+    const u32 tid = threadIdx.x;
+    u32* table = P.sort_hist + (size_t)row * kSortBins * P.Gs;
+    const u32 total = (u32)kSortBins * (u32)P.Gs;
+    if (tid == 0) {
+        carry = 0;
+        all_in_one = 0;
+    }
+    __syncthreads();
+    // is the digit the same for every key?  (then some bin's row of the table sums to k)
+    if (tid < kSortBins) {
+        u32 s = 0;
+        for (int w = 0; w < P.Gs; ++w) s += table[(size_t)tid * P.Gs + w];
+        if (s == (u32)P.k) all_in_one = 1;
+    }
+    __syncthreads();
+    const bool skip = all_in_one != 0;
+    if (!skip) {
+        for (u32 base = 0; base < total; base += kRowBlock) {
+            const u32 i = base + tid;
+            const u32 v = i < total ? table[i] : 0u;
+            const u32 incl = block_inclusive_scan<kRowBlock>(v, wsum);
+            const u32 c = carry;
+            if (i < total) table[i] = c + incl - v;
+            __syncthreads();
+            if (tid == kRowBlock - 1) carry = c + incl;
+            __syncthreads();
+        }
+    }
+    if (tid == 0) {
+        SortState* st = sort_state(P, row);
+        st->skip[j] = skip ? 1u : 0u;
+        st->cur[j + 1] = skip ? st->cur[j] : 1u - st->cur[j];
+    }
+}
+
+// stable scatter of pass j: elements keep their order within a bin
+template <int DT>
+__global__ void __launch_bounds__(kSortBlock) k_sort_scatter(Params P, int j) {
+    constexpr int W = kSortBlock / 64;
+    __shared__ u32 base[kSortBins];          // next free position of every bin for this workgroup
+    __shared__ u32 wcount[W][kSortBins];     // per wave: elements of each bin in the current tile; then their offset
+    const int row = blockIdx.y;
+    const SortState* st = sort_state(P, row);
+    if (st->skip[j]) return;
+    const u32 tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
+    const u64* src = sort_buffer(P, st->cur[j], row);
+    u64* dst = sort_buffer(P, 1u - st->cur[j], row);
+    const u32* table = P.sort_hist + (size_t)row * kSortBins * P.Gs;
+    if (tid < kSortBins) base[tid] = table[(size_t)tid * P.Gs + blockIdx.x];
+    u32 begin, end;
+    sort_chunk(P, blockIdx.x, begin, end);
+    for (u32 t0 = begin; t0 < end; t0 += kSortBlock) {
+        for (u32 q = tid; q < (u32)(W * kSortBins); q += kSortBlock) (&wcount[0][0])[q] = 0;
+        __syncthreads();
+        const u32 i = t0 + tid;
+        const bool have = i < end;
+        const u64 key = have ? src[i] : 0ull;
+        const u32 d = (u32)(key >> (8 * j)) & 255u;
+        // lanes of this wave that hold the same digit
+        u64 peers = ballot64(have);
+#pragma unroll
+        for (int b = 0; b < 8; ++b) {
+            const bool bit = ((d >> b) & 1u) != 0;
+            const u64 m = ballot64(bit);
+            peers &= bit ? m : ~m;
+        }
+        const u32 rank_in_wave = mbcnt64(peers);
+        if (have && rank_in_wave == 0) wcount[wave][d] = (u32)__popcll(peers);
+        __syncthreads();
+        // per bin (thread t owns bin t): offsets of the waves, in wave order, and the tile's total
+        u32 tile_total = 0;
+        if (tid < kSortBins) {
+#pragma unroll
+            for (int w = 0; w < W; ++w) {
+                const u32 c = wcount[w][tid];
+                wcount[w][tid] = tile_total;
+                tile_total += c;
+            }
+        }
+        __syncthreads();
+        if (have) dst[base[d] + wcount[wave][d] + rank_in_wave] = key;
+        __syncthreads();
+        if (tid < kSortBins) base[tid] += tile_total;
+    }
+}
+
+// sorted keys -> outputs; values are gathered from X by index
+template <int DT>
+__global__ void __launch_bounds__(kSortBlock) k_sort_unpack(Params P) {
+    const int row = blockIdx.y;
+    const u64* src = sort_buffer(P, sort_state(P, row)->cur[kSortPasses], row);
+    char* out_v = (char*)P.out_values + (size_t)row * (size_t)P.k * KeyOf<DT>::kBytes;
+    long long* out_i = P.out_indices + (size_t)row * (size_t)P.k;
+    const char* x = (const char*)P.keys + (size_t)row * (size_t)P.n * KeyOf<DT>::kBytes;
+    u32 begin, end;
+    sort_chunk(P, blockIdx.x, begin, end);
+    for (u32 i = begin + threadIdx.x; i < end; i += kSortBlock) {
+        const u32 idx = (u32)src[i];
+        out_i[i] = (long long)idx;
+        store_value<DT>(out_v, i, load_value<DT>(x, idx));
+    }
+}
+
+// Enqueue the sort of every row's output.
+template <int DT>
+static void launch_sort(const Params& P, hipStream_t st) {
+    if (P.k <= kSortSmall) {
+        hipLaunchKernelGGL((k_sort_small<DT>), dim3(P.batch), dim3(kRowBlock), 0, st, P);
+        return;
+    }
+    const dim3 grid(P.Gs, P.batch), block(kSortBlock);
+    hipLaunchKernelGGL((k_sort_pack<DT>), grid, block, 0, st, P);
+    for (int j = 0; j < kSortPasses; ++j) {
+        hipLaunchKernelGGL((k_sort_hist<DT>), grid, block, 0, st, P, j);
+        hipLaunchKernelGGL((k_sort_scan<DT>), dim3(P.batch), dim3(kRowBlock), 0, st, P, j);
+        hipLaunchKernelGGL((k_sort_scatter<DT>), grid, block, 0, st, P, j);
+    }
+    hipLaunchKernelGGL((k_sort_unpack<DT>), grid, block, 0, st, P);
+}

@@ -25,11 +25,11 @@ def values_to_bits(vals, dtype: int) -> np.ndarray:
 
 
 def gpu_topk(x_dev, dtype: int, k: int, largest: bool = True, scaling: bool = False, seed: int = 0,
-             tuning=None, workspace=None):
+             tuning=None, workspace=None, sorted: bool = False):
     """One call through the binding.  Returns (value words [batch,k], int64 indices [batch,k], traces, workspace)."""
     import torch
     from paper_2501_14336_amd import binding as B
-    vals, idx, ws = B.topk(x_dev, k, largest, scaling=scaling, seed=seed, tuning=tuning, workspace=workspace)
+    vals, idx, ws = B.topk(x_dev, k, largest, scaling=scaling, seed=seed, tuning=tuning, workspace=workspace, sorted=sorted)
     torch.cuda.synchronize()
     batch = 1 if x_dev.dim() == 1 else x_dev.shape[0]
     traces = B.read_trace(ws, batch)

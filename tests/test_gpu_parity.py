@@ -530,11 +530,65 @@ def test_kernels_stay_inside_the_workspace_and_the_outputs():
             _check_rows(b2, dtype, k, True, gv, idx.cpu().numpy(), B.read_trace(ws, batch))
 
 
+def _check_sorted(name, bits, dtype, k, largest, tuning=None, scaling=False):
+    """With the sorted-output flag the result equals the oracle's position by position (the oracle's order is best
+    first, lowest index first among equal elements)."""
+    _say("sorted:", name, bits.shape, "dtype", dtype, "k", k, "largest", largest, "tuning", tuning)
+    x = to_device(bits, dtype)
+    gv, gi, tr, _ = gpu_topk(x, dtype, k, largest, scaling=scaling, seed=5, tuning=tuning, sorted=True)
+    b2 = bits.reshape(1, -1) if bits.ndim == 1 else bits
+    wv, wi = oracle.topk(b2, dtype, k, largest)
+    for r in range(b2.shape[0]):
+        assert tr[r].error == 0 and tr[r].done
+        assert np.array_equal(gi[r], wi[r]), "row %d: indices differ from the oracle's order" % r
+        assert np.array_equal(gv[r], wv[r]), "row %d: value words differ from the oracle's order" % r
+
+
+@pytest.mark.parametrize("path", [1, 2])
+def test_sorted_output_small_k_in_lds(path):
+    T = dict(path=path)
+    x = W.normal(100003, 101)
+    for k in (1, 2, 50, 63, 64, 65, 1000, 4097, 8191, 8192):
+        for largest in (True, False):
+            _check_sorted("normal", x.view(np.uint32), F32, k, largest, T)
+    # ties: equal keys come out in index order; special values in their places (NaN first for largest)
+    for k in (10, 5000, 8192):
+        for largest in (True, False):
+            _check_sorted("duplicates", W.duplicates(50000, 102).view(np.uint32), F32, k, largest, T)
+            _check_sorted("specials", W.specials_ramp(30001, 103, with_nan=True).view(np.uint32), F32, k, largest, T)
+            _check_sorted("specials fp16", W.specials_ramp(30001, 104, dtype=np.float16, with_nan=True).view(np.uint16), F16,
+                          k, largest, T)
+            _check_sorted("constant", np.full(20000, np.float32(1.5)).view(np.uint32), F32, k, largest, T)
+    _check_sorted("logits batch", W.llm_logits(9, 40001, 105), BF16, 50, True, T)
+    _check_sorted("logits batch", W.llm_logits(9, 40001, 105), BF16, 8192, True, T)
+    _check_sorted("fp32 batch odd rows", W.normal(7 * 10007, 106).view(np.uint32).reshape(7, 10007), F32, 333, False, T)
+    _check_sorted("k = n", W.normal(5000, 107).view(np.uint32), F32, 5000, True, T)
+    _check_sorted("scaled", W.uniform_range(60000, 108, 128.6, 128.7).view(np.uint32), F32, 512, True, T, scaling=True)
+
+
+def test_sorted_output_large_k_radix_sort():
+    # beyond one workgroup's LDS: radix sort on the grid, chunks per workgroup, skipped passes
+    x = W.normal(300001, 111)
+    for k in (8193, 50000, 300001):
+        for largest in (True, False):
+            _check_sorted("normal", x.view(np.uint32), F32, k, largest)
+    _check_sorted("duplicates", W.duplicates(200003, 112).view(np.uint32), F32, 150000, True)
+    _check_sorted("duplicates", W.duplicates(200003, 112).view(np.uint32), F32, 150000, False, dict(path=2, wgs_per_row=7))
+    _check_sorted("constant", np.full(100000, np.float32(-2.0)).view(np.uint32), F32, 60000, True)
+    _check_sorted("specials", W.specials_ramp(100001, 113, with_nan=True).view(np.uint32), F32, 70000, True)
+    _check_sorted("specials", W.specials_ramp(100001, 113, with_nan=True).view(np.uint32), F32, 70000, False)
+    _check_sorted("bf16", W.llm_logits(3, 100001, 114), BF16, 20000, True)            # 16-bit keys: low key bytes skipped
+    _check_sorted("fp16", W.normal(2 * 70001, 115).astype(np.float16).view(np.uint16).reshape(2, 70001), F16, 70001, False)
+    _check_sorted("batch", W.normal(5 * 40000, 116).view(np.uint32).reshape(5, 40000), F32, 9000, True, dict(path=1))
+    _check_sorted("2^22", W.uniform_range(1 << 22, 117, -1e6, 1e6).view(np.uint32), F32, 1 << 20, True)
+
+
 # ------------------------------------------------------------------------------------------------ full sizes
 
 def test_config1_full():
     bits = W.config1().view(np.uint32)
     _run_and_check("config 1", bits, F32, 32, True)
+    _check_sorted("config 1", bits, F32, 32, True)
 
 
 def test_config2_full_k_sweep_both_directions():

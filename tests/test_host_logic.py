@@ -60,7 +60,7 @@ def test_workspace_bytes_scales_with_the_candidate_arrays():
 
 
 @pytest.mark.parametrize("args", [
-    dict(batch=0), dict(n=0), dict(k=0), dict(k=11), dict(dtype=3), dict(dtype=-1), dict(flags=4),
+    dict(batch=0), dict(n=0), dict(k=0), dict(k=11), dict(dtype=3), dict(dtype=-1), dict(flags=8),
     dict(n=(1 << 31) + 1, k=1),
     dict(tuning=dict(digit_bits=7)), dict(tuning=dict(digit_bits=13)), dict(tuning=dict(path=4)), dict(tuning=dict(prefilter=2)),
     dict(tuning=dict(prefilter=-2)),
@@ -82,7 +82,7 @@ def _select(keys=0x10000, batch=1, n=1000, k=10, dtype=0, largest=True, flags=0,
 
 def test_select_validates_on_the_host_before_launching():
     for bad in (dict(keys=0), dict(out_v=0), dict(out_i=0), dict(ws=0), dict(k=0), dict(k=1001), dict(batch=0),
-                dict(dtype=7), dict(flags=4)):
+                dict(dtype=7), dict(flags=8)):
         with pytest.raises(B.RtopkError) as e:
             _select(**bad)
         assert e.value.status == 1, bad
