@@ -142,6 +142,29 @@ rtopk_status rtopk_select_ex(const void* keys, int64_t batch, int64_t n, int64_t
                              const rtopk_tuning* tuning);
 
 /*
+ * Ragged batch (paper Section 3.2.2: tasks of different lengths stored one after the other, with the padding a
+ * 16-byte load needs supplied on demand; the ablation of Section 5.3.3 uses such a batch): row r is
+ * keys[row_offsets[r] .. row_offsets[r + 1]) of ONE array and has its own k, row_k[r].
+ *
+ *   keys         device, the rows one after the other, element type dt, aligned to the element size
+ *   row_offsets  device, batch + 1 int64, in elements, non-decreasing; rows need no alignment
+ *   row_k        device, batch int64, 0 <= row_k[r] <= length of row r
+ *   n_max, k_max host: no row is longer than n_max, no row_k exceeds k_max; 1 <= k_max <= n_max <= RTOPK_MAX_N.
+ *                They size the workspace -- rtopk_workspace_bytes_ex(batch, n_max, k_max, dt, flags, tuning) --
+ *                and choose the kernels; the result does not depend on them.
+ *   out_values   device, [batch][k_max]; out_indices device, [batch][k_max] int64: row r's row_k[r] results are
+ *                the first entries of output row r (positions within the row, from 0); the rest is left alone.
+ * Everything else as in rtopk_select_ex.  The two arrays live on the device, so they are checked there: a row
+ * whose k is 0 (or that is empty) is skipped and has no pass records; a row_k beyond the row's length or k_max, a
+ * negative one, or a row longer than n_max is cut down to what fits and reported as bit 8 of that row's
+ * rtopk_row_trace.error.
+ */
+rtopk_status rtopk_select_ragged(const void* keys, const int64_t* row_offsets, const int64_t* row_k, int64_t batch,
+                                 int64_t n_max, int64_t k_max, rtopk_dtype dt, int largest, uint32_t flags, uint64_t seed,
+                                 void* out_values, int64_t* out_indices, void* workspace, size_t workspace_bytes,
+                                 void* hip_stream, const rtopk_tuning* tuning);
+
+/*
  * rtopk_select for callers that cannot allocate device memory and have no workspace to pass: code under
  * HIP graph capture, tight serving loops (top-k over a batch of logit rows at every decoding step),
  * harnesses that forbid hipMalloc.  Identical to rtopk_select in arguments, defaults, result and error

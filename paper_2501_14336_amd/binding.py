@@ -31,6 +31,7 @@ EXPORTS = (
     "rtopk_select_ex",
     "rtopk_select_events",
     "rtopk_select_static",
+    "rtopk_select_ragged",
     "rtopk_status_string",
     "rtopk_version",
 )
@@ -158,6 +159,9 @@ def load():
         lib.rtopk_select_events.argtypes = lib.rtopk_select_ex.argtypes + [ctypes.POINTER(ctypes.c_void_p)]
         lib.rtopk_select_static.restype = ctypes.c_int
         lib.rtopk_select_static.argtypes = [vp, i64, i64, i64, ctypes.c_int, ctypes.c_int, u32, u64, vp, vp, vp]
+        lib.rtopk_select_ragged.restype = ctypes.c_int
+        lib.rtopk_select_ragged.argtypes = [vp, vp, vp, i64, i64, i64, ctypes.c_int, ctypes.c_int, u32, u64, vp, vp, vp, sz, vp,
+                                            ctypes.POINTER(RtopkTuning)]
         lib.rtopk_status_string.restype = ctypes.c_char_p
         lib.rtopk_status_string.argtypes = [ctypes.c_int]
         lib.rtopk_version.restype = ctypes.c_char_p
@@ -224,6 +228,36 @@ def rtopk_select_static(keys_ptr: int, batch: int, n: int, k: int, dtype: int, l
                                     out_indices_ptr, stream)
     if st != RTOPK_OK:
         raise RtopkError(st, rtopk_status_string(st))
+
+
+def rtopk_select_ragged(keys_ptr: int, row_offsets_ptr: int, row_k_ptr: int, batch: int, n_max: int, k_max: int, dtype: int,
+                        largest: bool, flags: int, seed: int, out_values_ptr: int, out_indices_ptr: int,
+                        workspace_ptr: int, workspace_bytes: int, stream: int = 0, tuning=None) -> None:
+    """Raw call for a ragged batch: rows of different lengths in one array, each with its own k (device arrays)."""
+    st = load().rtopk_select_ragged(keys_ptr, row_offsets_ptr, row_k_ptr, batch, n_max, k_max, dtype, 1 if largest else 0,
+                                    flags, seed, out_values_ptr, out_indices_ptr, workspace_ptr, workspace_bytes, stream,
+                                    _tuning_ptr(tuning))
+    if st != RTOPK_OK:
+        raise RtopkError(st, rtopk_status_string(st))
+
+
+def topk_ragged(x, row_offsets, row_k, n_max: int, k_max: int, largest: bool = True, scaling: bool = False, seed: int = 0,
+                tuning=None, sorted: bool = False):
+    """Top-k of every row of a ragged batch: ``x`` is the 1-D concatenation of the rows (a CUDA/HIP tensor),
+    ``row_offsets`` (batch + 1) and ``row_k`` (batch) are int64 CUDA/HIP tensors.  Returns (values [batch, k_max],
+    indices [batch, k_max] filled with -1 beyond each row's k, workspace)."""
+    import torch
+    batch = row_k.numel()
+    code = _torch_dtype_code(x)
+    flags = (RTOPK_FLAG_SCALING if scaling else 0) | (RTOPK_FLAG_SORTED if sorted else 0)
+    need = rtopk_workspace_bytes(batch, n_max, k_max, code, flags, tuning)
+    ws = torch.empty(need, dtype=torch.uint8, device=x.device)
+    vals = torch.zeros((batch, k_max), dtype=x.dtype, device=x.device)
+    idx = torch.full((batch, k_max), -1, dtype=torch.int64, device=x.device)
+    stream = torch.cuda.current_stream(x.device).cuda_stream
+    rtopk_select_ragged(x.data_ptr(), row_offsets.data_ptr(), row_k.data_ptr(), batch, n_max, k_max, code, largest, flags,
+                        seed, vals.data_ptr(), idx.data_ptr(), ws.data_ptr(), ws.numel(), stream, tuning)
+    return vals, idx, ws
 
 
 # ---------------------------------------------------------------------------

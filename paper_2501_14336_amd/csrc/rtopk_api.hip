@@ -251,11 +251,14 @@ rtopk_status rtopk_workspace_bytes(int64_t batch, int64_t n, int64_t k, rtopk_dt
     return rtopk_workspace_bytes_ex(batch, n, k, dt, flags, nullptr, bytes_out);
 }
 
-rtopk_status rtopk_select_events(const void* keys, int64_t batch, int64_t n, int64_t k, rtopk_dtype dt, int largest,
-                                 uint32_t flags, uint64_t seed, void* out_values, int64_t* out_indices,
-                                 void* workspace, size_t workspace_bytes, void* hip_stream,
-                                 const rtopk_tuning* tuning, void* const* events) {
+// Every entry point ends here.  row_offsets / row_k: null, or the ragged batch's device arrays (n and k are then the
+// largest row length and the largest k).
+static rtopk_status select_impl(const void* keys, const int64_t* row_offsets, const int64_t* row_k, int64_t batch, int64_t n,
+                                int64_t k, rtopk_dtype dt, int largest, uint32_t flags, uint64_t seed, void* out_values,
+                                int64_t* out_indices, void* workspace, size_t workspace_bytes, void* hip_stream,
+                                const rtopk_tuning* tuning, void* const* events) {
     if (!keys || !out_values || !out_indices || !workspace) return RTOPK_ERR_INVALID_ARG;
+    if ((row_offsets == nullptr) != (row_k == nullptr)) return RTOPK_ERR_INVALID_ARG;
     Config c;
     rtopk_status s = make_config(batch, n, k, dt, largest, flags, tuning, &c);
     if (s != RTOPK_OK) return s;
@@ -270,6 +273,8 @@ rtopk_status rtopk_select_events(const void* keys, int64_t batch, int64_t n, int
     memset(&P, 0, sizeof(P));
     char* ws = (char*)workspace;
     P.keys = keys;
+    P.row_offsets = (const long long*)row_offsets;
+    P.row_k = (const long long*)row_k;
     P.out_values = out_values;
     P.out_indices = (long long*)out_indices;
     P.state = (rtopk_row_trace*)(ws + L.state_off);
@@ -304,7 +309,7 @@ rtopk_status rtopk_select_events(const void* keys, int64_t batch, int64_t n, int
         // (not when the second sweep writes a lot: with k = 2^24 and 2^27 of 2^28 the kept tail made the call
         // 3 % and 7 % slower instead of 4 % faster)
         const bool small_output = (size_t)k * (size_t)(eb + 8) <= ((size_t)32 << 20);
-        if (batch == 1 && small_output && row_tiles > keep_tiles) P.keep_from_tile = (u32)(row_tiles - keep_tiles);
+        if (batch == 1 && !row_offsets && small_output && row_tiles > keep_tiles) P.keep_from_tile = (u32)(row_tiles - keep_tiles);
     }
     P.seed = seed;
     for (int i = 0; i < c.npass; ++i) P.pass[i] = c.pass[i];
@@ -318,6 +323,24 @@ rtopk_status rtopk_select_events(const void* keys, int64_t batch, int64_t n, int
         case RTOPK_BF16: return launch_bf16(P, c, false, st, events);
     }
     return RTOPK_ERR_INVALID_ARG;
+}
+
+rtopk_status rtopk_select_events(const void* keys, int64_t batch, int64_t n, int64_t k, rtopk_dtype dt, int largest,
+                                 uint32_t flags, uint64_t seed, void* out_values, int64_t* out_indices,
+                                 void* workspace, size_t workspace_bytes, void* hip_stream,
+                                 const rtopk_tuning* tuning, void* const* events) {
+    return select_impl(keys, nullptr, nullptr, batch, n, k, dt, largest, flags, seed, out_values, out_indices, workspace,
+                       workspace_bytes, hip_stream, tuning, events);
+}
+
+rtopk_status rtopk_select_ragged(const void* keys, const int64_t* row_offsets, const int64_t* row_k, int64_t batch,
+                                 int64_t n_max, int64_t k_max, rtopk_dtype dt, int largest, uint32_t flags, uint64_t seed,
+                                 void* out_values, int64_t* out_indices, void* workspace, size_t workspace_bytes,
+                                 void* hip_stream, const rtopk_tuning* tuning) {
+    if (!row_offsets || !row_k) return RTOPK_ERR_INVALID_ARG;
+    if (((uintptr_t)row_offsets % 8) || ((uintptr_t)row_k % 8)) return RTOPK_ERR_UNSUPPORTED;
+    return select_impl(keys, row_offsets, row_k, batch, n_max, k_max, dt, largest, flags, seed, out_values, out_indices,
+                       workspace, workspace_bytes, hip_stream, tuning, nullptr);
 }
 
 rtopk_status rtopk_select_ex(const void* keys, int64_t batch, int64_t n, int64_t k, rtopk_dtype dt, int largest,

@@ -38,7 +38,9 @@ struct Params {
     unsigned long long* dbg; // [batch][G][16]      optional per-workgroup timestamps (diagnostic builds only)
     u32* sort_hist;          // [batch][256][Gs]    sorted output of long rows: per-chunk digit counts, then offsets
     void* sort_state;        // [batch] records of 128 bytes: which array holds the keys, which passes are skipped
-    long long n, k;
+    long long n, k;          // row length and k; with row_offsets: the LARGEST row length and k (outputs are [batch][k] either way)
+    const long long* row_offsets;  // ragged batch (device, batch + 1 entries, in elements): row r is keys[row_offsets[r] .. row_offsets[r+1]); else null
+    const long long* row_k;        // ragged batch (device, batch entries): k of every row
     int batch, G, Gs;
     u32 dirmask;             // 0 for "largest"; all key bits set for "smallest" (complements the key)
     u32 idx_max;             // 2^ceil(log2 n) - 1: the index digit source is idx_max - index
@@ -54,6 +56,35 @@ struct Params {
 
 __device__ __forceinline__ rtopk_row_trace* row_state(const Params& P, int row) {
     return (rtopk_row_trace*)((char*)P.state + (size_t)row * RTOPK_TRACE_STRIDE);
+}
+
+// One row of the batch: where its elements start, how many there are, how many are wanted.  A batch is either
+// [batch][n] with one k, or ragged (Section 3.2.2): rows of any length one after the other in one array, each with
+// its own k.  In a ragged batch a row with k = 0 (or no elements) is skipped by every kernel; a k beyond the row's
+// length or beyond the output row is cut down to it and reported in the row's record (error bit 8).
+struct RowShape {
+    const char* x;
+    u32 n, k;
+    bool bad;
+};
+template <int ELEM_BYTES>
+__device__ __forceinline__ RowShape row_shape(const Params& P, int row) {
+    RowShape r;
+    r.bad = false;
+    if (P.row_offsets) {
+        const long long o0 = P.row_offsets[row], o1 = P.row_offsets[row + 1];
+        long long n = o1 - o0, k = P.row_k[row];
+        if (n < 0 || n > P.n) { r.bad = true; n = n < 0 ? 0 : P.n; }
+        if (k < 0 || k > n || k > P.k) { r.bad = true; k = k < 0 ? 0 : (n < P.k ? n : P.k); }
+        r.x = (const char*)P.keys + (size_t)o0 * ELEM_BYTES;
+        r.n = (u32)n;
+        r.k = (u32)k;
+    } else {
+        r.x = (const char*)P.keys + (size_t)row * (size_t)P.n * ELEM_BYTES;
+        r.n = (u32)P.n;
+        r.k = (u32)P.k;
+    }
+    return r;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -192,9 +223,9 @@ struct KeySource {
     u32 n;
     u64 nvec;  // vectors covering [abase, row end)
 
-    __device__ __forceinline__ void init(const void* keys, long long n_, int row) {
-        const char* p = (const char*)keys + (size_t)row * (size_t)n_ * kElemBytes;
-        uintptr_t a = (uintptr_t)p;
+    __device__ __forceinline__ void init(const RowShape& rs) {
+        uintptr_t a = (uintptr_t)rs.x;
+        const u32 n_ = rs.n;
         abase = (const uint4*)(a & ~(uintptr_t)15);
         lead = (u32)((a & 15) / kElemBytes);
         n = (u32)n_;

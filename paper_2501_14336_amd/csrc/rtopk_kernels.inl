@@ -108,11 +108,11 @@ constexpr u32 kWindowArrayBit = 24;
 constexpr u32 kRankCap = 512;
 constexpr int SRC_RANK = 3;  // `window` source code of the record the ranking step leaves
 
-__device__ __forceinline__ PassEntry pass_entry(const Params& P, const rtopk_row_trace* st, int p) {
+__device__ __forceinline__ PassEntry pass_entry(const Params& P, const rtopk_row_trace* st, int p, const RowShape& rs) {
     PassEntry e;
     if (p == 0) {
-        e.cand = (u32)P.n;
-        e.k_rem = (u32)P.k;
+        e.cand = rs.n;
+        e.k_rem = rs.k;
         e.out_before = 0;
         e.finished = false;
         e.prev_multi = true;
@@ -360,7 +360,7 @@ struct RowSample {
     __device__ __forceinline__ u32 tile(u32 j) const { return first + j * stride; }
 };
 template <class Source>
-__device__ __forceinline__ RowSample row_sample(const Source& src, const Params& P) {
+__device__ __forceinline__ RowSample row_sample(const Source& src, const Params& P, u32 src_k) {
     RowSample r;
     u32 f0, f1;
     src.full_range(f0, f1);
@@ -368,7 +368,7 @@ __device__ __forceinline__ RowSample row_sample(const Source& src, const Params&
     r.stride = P.pre_stride;
     r.tiles = (f1 - f0 + r.stride - 1u) / r.stride;
     r.elems = r.tiles * (u32)(Source::kTileVecs * Source::E);
-    const u64 ks = ((u64)P.k * r.elems + (u64)P.n - 1u) / (u64)P.n;
+    const u64 ks = ((u64)src_k * r.elems + (u64)src.n - 1u) / (u64)src.n;
     r.rank = ks + ks / 8u + 8u * ((u64)sqrtf((float)ks) + 2u) + 16u;
     return r;
 }
@@ -484,7 +484,7 @@ __device__ __forceinline__ Selection hist_phase(const Source& src, const Params&
         };
         if (!SINGLE && P.pre_stride != 0) {
             // before a prefilter sweep only a sample of the row is counted: every pre_stride-th full tile
-            const RowSample sample = row_sample(src, P);
+            const RowSample sample = row_sample(src, P, e.k_rem);
             typename Source::Tile a, b;
             const auto plain = src.plain();
             u32 j = wg;
@@ -903,7 +903,7 @@ __device__ __forceinline__ bool pass_pair_is_one_window(const Params& P, int p) 
 // key's bin (sel0->bin), `sel` is pass 1's selectBin on those counts, and this one sweep stands for both passes: it
 // classifies by the two digits taken as one (better than bin 0's digit, or in it and better than bin 1's: a winner).
 template <class Source, int DT, int SRC, int B, bool SINGLE, class Resident = NoResident, bool PRE = false, int ST = kStage>
-__device__ __forceinline__ PassEntry classify_phase(const Source& src, const Params& P, int p, int row, u32 wg, u32 G,
+__device__ __forceinline__ PassEntry classify_phase(const Source& src, const Params& P, int p, int row, u32 row_k, u32 wg, u32 G,
                                                     const PassEntry& e, rtopk_row_trace* st, float a_s, Shared<B, ST>& sm,
                                                     u32 where, const Selection& sel, u32 records, bool own_segment,
                                                     const Resident& resident = Resident(), const Selection* sel0 = nullptr) {
@@ -962,7 +962,9 @@ __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Par
     if (!PRE && wg == 0 && tid == 0) {
         if (sel0) {
             // pass 0's record: what its selectBin decided; its winners leave in this sweep
-            const PassEntry e0 = pass_entry(P, st, 0);
+            PassEntry e0 = e;  // (only what a record takes from it matters)
+            e0.cand = st->pre_kept;
+            e0.out_before = 0;
             write_pass_record(st, 0, P.pass[0], e0, *sel0, where, e.src_array);
             st->pass_rec[0].cand_before = st->pre_kept;
             st->pre_merged = 1u;
@@ -989,7 +991,7 @@ __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Par
     o.out_i = P.out_indices + (size_t)row * (size_t)P.k;
     o.cand_out = P.cand[out_array] + (size_t)row * P.cand_stride;
     o.cand_lds = to_rank ? (uint2*)sm.hist : nullptr;
-    o.kk = (u32)P.k;
+    o.kk = row_k;
     o.ncap = (u32)P.cand_stride;
     // (with sel0: the window holds pass p - 1's digit above pass p's own)
     o.b = sel0 ? (sel0->bin << own_pi.bits) | sel.bin : sel.bin;
@@ -1226,18 +1228,19 @@ __device__ __forceinline__ u64 mix64(u64 z) {
 
 // Called by every thread of a workgroup of at least 128 threads; returns a_s to thread 0 only.
 template <int DT>
-__device__ __forceinline__ float init_row(const Params& P, int row, rtopk_row_trace* st) {
+__device__ __forceinline__ float init_row(const Params& P, int row, rtopk_row_trace* st, const RowShape& rs) {
     static_assert(sizeof(rtopk_row_trace) / 4 <= 128 && offsetof(rtopk_row_trace, a_s) == 0, "trace layout");
     u32* w = (u32*)st;
-    if (threadIdx.x >= 1 && threadIdx.x < sizeof(rtopk_row_trace) / 4) w[threadIdx.x] = 0;
+    if (threadIdx.x >= 2 && threadIdx.x < sizeof(rtopk_row_trace) / 4) w[threadIdx.x] = 0;
     float a_s = 0.0f;
     if (threadIdx.x == 0) {
-        if (DT == RTOPK_F32 && (P.flags & RTOPK_FLAG_SCALING)) {
-            const u64 j = mix64(P.seed + 0x9E3779B97F4A7C15ull * (u64)(row + 1)) % (u64)P.n;
-            const u32 bits = ((const u32*)P.keys)[(size_t)row * (size_t)P.n + j];
+        if (DT == RTOPK_F32 && (P.flags & RTOPK_FLAG_SCALING) && rs.n != 0) {
+            const u64 j = mix64(P.seed + 0x9E3779B97F4A7C15ull * (u64)(row + 1)) % (u64)rs.n;
+            const u32 bits = ((const u32*)rs.x)[j];
             if ((bits & 0x7f800000u) != 0x7f800000u) a_s = __uint_as_float(bits);  // finite only
         }
         st->a_s = a_s;
+        st->error = rs.bad ? 8u : 0u;
     }
     return a_s;
 }
@@ -1249,7 +1252,7 @@ __global__ void __launch_bounds__(256) k_init(Params P) {
         u32* ghist = P.ghist + ((size_t)h * P.batch + row) * kMaxBins;
         for (int j = threadIdx.x; j < kMaxBins; j += 256) ghist[j] = 0;
     }
-    init_row<DT>(P, row, row_state(P, row));
+    init_row<DT>(P, row, row_state(P, row), row_shape<KeyOf<DT>::kBytes>(P, row));
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1267,25 +1270,29 @@ template <int DT, int SRC, bool NT>
 __global__ void __launch_bounds__(kGridBlock) k_hist_keys(Params P) {
     __shared__ Shared<kGridBlock> sm;
     const int row = blockIdx.y;
+    const RowShape rs = row_shape<KeyOf<DT>::kBytes>(P, row);
+    if (rs.k == 0) return;  // (ragged batches: an empty row, or nothing wanted from it)
     rtopk_row_trace* st = row_state(P, row);
     KeySource<DT, kGridBlock, key_vecs<DT>(), NT> src;
-    src.init(P.keys, P.n, row);
+    src.init(rs);
     hist_phase<decltype(src), DT, SRC, kGridBlock, false>(src, P, 0, row, blockIdx.x, gridDim.x, st->a_s,
-                                                          pass_entry(P, st, 0), st, sm);
+                                                          pass_entry(P, st, 0, rs), st, sm);
 }
 
 template <int DT, int SRC, bool NT>
 __global__ void __launch_bounds__(kGridBlock) k_classify_keys(Params P) {
     __shared__ Shared<kGridBlock> sm;
     const int row = blockIdx.y;
+    const RowShape rs = row_shape<KeyOf<DT>::kBytes>(P, row);
+    if (rs.k == 0) return;  // (ragged batches: an empty row, or nothing wanted from it)
     rtopk_row_trace* st = row_state(P, row);
-    const PassEntry e = pass_entry(P, st, 0);
+    const PassEntry e = pass_entry(P, st, 0, rs);
     KeySource<DT, kGridBlock, key_vecs<DT>(), NT> src;
-    src.init(P.keys, P.n, row);
+    src.init(rs);
     const u32 ntiles = src.ntiles();
     // every workgroup repeats selectBin on the row's global histogram (cheap, and it spares a grid-wide hand-off)
     const Selection sel = select_pass<kGridBlock>(PlainCounts{global_hist(P, 0, row)}, 1 << P.pass[0].bits, e, sm, st);
-    classify_phase<decltype(src), DT, SRC, kGridBlock, false>(src, P, 0, row, blockIdx.x, gridDim.x, e, st, st->a_s, sm, 1u,
+    classify_phase<decltype(src), DT, SRC, kGridBlock, false>(src, P, 0, row, rs.k, blockIdx.x, gridDim.x, e, st, st->a_s, sm, 1u,
                                                               sel, ntiles < gridDim.x ? ntiles : gridDim.x, false);
 }
 
@@ -1306,11 +1313,13 @@ template <int DT, int SRC, bool NT, bool BIG>
 __global__ void __launch_bounds__(kGridBlock) k_prefilter_keys(Params P) {
     __shared__ Shared<kGridBlock, BIG ? kStageBig : kStage> sm;
     const int row = blockIdx.y;
+    const RowShape rs = row_shape<KeyOf<DT>::kBytes>(P, row);
+    if (rs.k == 0) return;  // (ragged batches: an empty row, or nothing wanted from it)
     rtopk_row_trace* st = row_state(P, row);
-    PassEntry e = pass_entry(P, st, 0);
+    PassEntry e = pass_entry(P, st, 0, rs);
     KeySource<DT, kGridBlock, key_vecs<DT>(), NT> src;
-    src.init(P.keys, P.n, row);
-    const RowSample sample = row_sample(src, P);
+    src.init(rs);
+    const RowSample sample = row_sample(src, P, rs.k);
     // a rank beyond the sample (or an empty sample) selects nothing: bin 0, everything is kept
     e.k_rem = sample.rank < (u64)sample.elems ? (u32)sample.rank : sample.elems + 1u;
     bool ignored;
@@ -1322,8 +1331,8 @@ __global__ void __launch_bounds__(kGridBlock) k_prefilter_keys(Params P) {
     constexpr u32 kCrowded = DT == RTOPK_F32 ? 8u : 16u;
     if ((u64)(sel.above + sel.inside) * kCrowded > (u64)sample.elems) sel.bin = 1u << P.pass[0].bits;
     if (blockIdx.x == 0 && threadIdx.x == 0) st->pre_bound = sel.bin;
-    e.k_rem = (u32)P.k;
-    classify_phase<decltype(src), DT, SRC, kGridBlock, false, NoResident, true>(src, P, 0, row, blockIdx.x, gridDim.x, e, st,
+    e.k_rem = rs.k;
+    classify_phase<decltype(src), DT, SRC, kGridBlock, false, NoResident, true>(src, P, 0, row, rs.k, blockIdx.x, gridDim.x, e, st,
                                                                                 st->a_s, sm, 1u, sel, gridDim.x, false);
 }
 
@@ -1335,8 +1344,10 @@ template <int DT, bool NT>
 __global__ void __launch_bounds__(kGridBlock) k_pass0_after_prefilter(Params P) {
     __shared__ Shared<kGridBlock> sm;
     const int row = blockIdx.y;
+    const RowShape rs = row_shape<KeyOf<DT>::kBytes>(P, row);
+    if (rs.k == 0) return;  // (ragged batches: an empty row, or nothing wanted from it)
     rtopk_row_trace* st = row_state(P, row);
-    const PassEntry e = pass_entry(P, st, 0);
+    const PassEntry e = pass_entry(P, st, 0, rs);
     const Selection sel = select_pass<kGridBlock>(PlainCounts{global_hist(P, 0, row)}, 1 << P.pass[0].bits, e, sm, st);
     const u32 bound = st->pre_bound;
     if (sel.bin >= bound) {
@@ -1357,19 +1368,19 @@ __global__ void __launch_bounds__(kGridBlock) k_pass0_after_prefilter(Params P) 
             __syncthreads();  // everybody has read the first selectBin's result: its LDS words may be reused
             const Selection sel1 = select_pass<kGridBlock>(PlainCounts{hist_buffer(P, kHistSecond, row)}, 1 << P.pass[1].bits,
                                                            e1, sm, st);
-            classify_phase<decltype(src), DT, SRC_RUNTIME, kGridBlock, false>(src, P, 1, row, blockIdx.x, gridDim.x, e1, st,
+            classify_phase<decltype(src), DT, SRC_RUNTIME, kGridBlock, false>(src, P, 1, row, rs.k, blockIdx.x, gridDim.x, e1, st,
                                                                               st->a_s, sm, 1u, sel1, gridDim.x, true,
                                                                               NoResident(), &sel);
         } else {
-            classify_phase<decltype(src), DT, SRC_RUNTIME, kGridBlock, false>(src, P, 0, row, blockIdx.x, gridDim.x, e, st,
+            classify_phase<decltype(src), DT, SRC_RUNTIME, kGridBlock, false>(src, P, 0, row, rs.k, blockIdx.x, gridDim.x, e, st,
                                                                               st->a_s, sm, 1u, sel, gridDim.x, true);
         }
     } else {
         if (blockIdx.x == 0 && threadIdx.x == 0) st->pre_missed = bound == (1u << P.pass[0].bits) ? 2u : 1u;
         KeySource<DT, kGridBlock, key_vecs<DT>(), NT> src;
-        src.init(P.keys, P.n, row);
+        src.init(rs);
         const u32 ntiles = src.ntiles();
-        classify_phase<decltype(src), DT, SRC_KEY, kGridBlock, false>(src, P, 0, row, blockIdx.x, gridDim.x, e, st, st->a_s,
+        classify_phase<decltype(src), DT, SRC_KEY, kGridBlock, false>(src, P, 0, row, rs.k, blockIdx.x, gridDim.x, e, st, st->a_s,
                                                                       sm, 1u, sel, ntiles < gridDim.x ? ntiles : gridDim.x, false);
     }
 }
@@ -1379,18 +1390,20 @@ template <int DT>
 __global__ void __launch_bounds__(kGridBlock) k_classify_cand(Params P, int p) {
     __shared__ Shared<kGridBlock> sm;
     const int row = blockIdx.y;
+    const RowShape rs = row_shape<KeyOf<DT>::kBytes>(P, row);
+    if (rs.k == 0) return;  // (ragged batches: an empty row, or nothing wanted from it)
     rtopk_row_trace* st = row_state(P, row);
     // (pass 1 may have been done together with pass 0, by the launch before this one: st->pre_merged, which that
     // launch wrote and this one only reads)
     if (p == 1 && st->pre_merged != 0u) return;
-    const PassEntry e = pass_entry(P, st, p);
+    const PassEntry e = pass_entry(P, st, p, rs);
     if (!multi_runs_pass(P, e, p)) return;
     const u32* seg = seg_records(P, e.src_array, row) + (size_t)blockIdx.x * 2;
     CandSource<kGridBlock, kVecs> src;
     src.init(P.cand[e.src_array] + (size_t)row * P.cand_stride, seg[0], seg[1], (u32)P.cand_stride);
     // its own tiles only: the segment is this workgroup's alone
     const Selection sel = select_pass<kGridBlock>(PlainCounts{global_hist(P, p, row)}, 1 << P.pass[p].bits, e, sm, st);
-    classify_phase<decltype(src), DT, SRC_RUNTIME, kGridBlock, false>(src, P, p, row, blockIdx.x, gridDim.x, e, st, st->a_s,
+    classify_phase<decltype(src), DT, SRC_RUNTIME, kGridBlock, false>(src, P, p, row, rs.k, blockIdx.x, gridDim.x, e, st, st->a_s,
                                                                       sm, 1u, sel, gridDim.x, true);
 }
 
@@ -1404,8 +1417,8 @@ __global__ void __launch_bounds__(kGridBlock) k_classify_cand(Params P, int p) {
 // written in rank order.  It stands for every digit pass still to come (same winners as Algorithm 1's
 // remaining iterations would find, since those order by exactly these bits), and leaves one record.
 template <int DT>
-__device__ __forceinline__ void rank_finish(const Params& P, int row, rtopk_row_trace* st, Shared<kRowBlock>& sm, int p,
-                                            const PassEntry& e, u32 where) {
+__device__ __forceinline__ void rank_finish(const Params& P, int row, u32 row_k, rtopk_row_trace* st, Shared<kRowBlock>& sm,
+                                            int p, const PassEntry& e, u32 where) {
     static_assert(kRankCap + 8 <= (u32)kRowBlock && kRankCap * 16 + 64 <= sizeof(sm.hist), "one lane per candidate");
     const u32 tid = threadIdx.x;
     const u32 C = e.cand;
@@ -1437,7 +1450,7 @@ __device__ __forceinline__ void rank_finish(const Params& P, int row, rtopk_row_
         }
         if (tid < C && rank < e.k_rem) {
             const u32 pos = e.out_before + rank;
-            if (pos < (u32)P.k) {
+            if (pos < row_k) {
                 store_value<DT>((char*)P.out_values + (size_t)row * (size_t)P.k * KeyOf<DT>::kBytes, pos, mine.x);
                 P.out_indices[(size_t)row * (size_t)P.k + pos] = (long long)mine.y;
             }
@@ -1460,13 +1473,13 @@ __device__ __forceinline__ void rank_finish(const Params& P, int row, rtopk_row_
 // state e.  `hist_from` says where pass p's histogram is; every later pass finds its counts in LDS, left there
 // by the pass before it.
 template <int DT>
-__device__ __forceinline__ void finish_row(const Params& P, int row, rtopk_row_trace* st, float a_s,
+__device__ __forceinline__ void finish_row(const Params& P, int row, const RowShape& rs, rtopk_row_trace* st, float a_s,
                                            Shared<kRowBlock>& sm, int p, PassEntry e, int hist_from, u32 where) {
     for (; p < P.npass; ++p) {
         if (e.finished) return;
         __syncthreads();  // the previous pass's candidates are visible to the whole workgroup
         if (e.cand <= kRankCap && P.pass[p].src != SRC_SCALED) {
-            rank_finish<DT>(P, row, st, sm, p, e, where);
+            rank_finish<DT>(P, row, rs.k, st, sm, p, e, where);
             return;
         }
         CandSource<kRowBlock, kVecs> src;
@@ -1475,7 +1488,7 @@ __device__ __forceinline__ void finish_row(const Params& P, int row, rtopk_row_t
         const Selection sel = hist_from == HIST_IN_GLOBAL
             ? select_pass<kRowBlock>(PlainCounts{global_hist(P, p, row)}, nb, e, sm, st)
             : select_pass<kRowBlock>(PlainCounts{sm.hist}, nb, e, sm, st);
-        e = classify_phase<decltype(src), DT, SRC_RUNTIME, kRowBlock, true>(src, P, p, row, 0u, 1u, e, st, a_s, sm, where,
+        e = classify_phase<decltype(src), DT, SRC_RUNTIME, kRowBlock, true>(src, P, p, row, rs.k, 0u, 1u, e, st, a_s, sm, where,
                                                                             sel, 1u, true);
         hist_from = HIST_IN_LDS;
     }
@@ -1487,12 +1500,14 @@ template <int DT>
 __global__ void __launch_bounds__(kRowBlock) k_finish(Params P) {
     __shared__ Shared<kRowBlock> sm;
     const int row = blockIdx.x;
+    const RowShape rs = row_shape<KeyOf<DT>::kBytes>(P, row);
+    if (rs.k == 0) return;  // (ragged batches: an empty row, or nothing wanted from it)
     rtopk_row_trace* st = row_state(P, row);
     int p = 0;
     while (p < P.npass && st->pass_rec[p].where != 0u) ++p;  // first pass the grid kernels left undone
     if (p == P.npass) return;
-    const PassEntry e = pass_entry(P, st, p);
-    finish_row<DT>(P, row, st, st->a_s, sm, p, e, HIST_IN_GLOBAL, 2u);  // its histogram was published by the pass before it
+    const PassEntry e = pass_entry(P, st, p, rs);
+    finish_row<DT>(P, row, rs, st, st->a_s, sm, p, e, HIST_IN_GLOBAL, 2u);  // its histogram was published by the pass before it
 }
 
 // Whole selection of one row in one kernel (many short rows: no global atomics, no extra launches).
@@ -1503,17 +1518,19 @@ __global__ void __launch_bounds__(kRowBlock) k_row(Params P, bool only_redo) {
     const int row = blockIdx.x;
     rtopk_row_trace* st = row_state(P, row);
     if (only_redo && st->redo != 1u) return;
-    const float drawn = init_row<DT>(P, row, st);
+    const RowShape rs = row_shape<KeyOf<DT>::kBytes>(P, row);
+    const float drawn = init_row<DT>(P, row, st, rs);
+    if (rs.k == 0) return;  // (ragged batches: an empty row, or nothing wanted from it)
     if (threadIdx.x == 0) sm.a_s = drawn;
     __syncthreads();
     const float a_s = sm.a_s;
-    const PassEntry e = pass_entry(P, st, 0);
+    const PassEntry e = pass_entry(P, st, 0, rs);
     KeySource<DT, kRowBlock, key_vecs<DT>(), false> src;
-    src.init(P.keys, P.n, row);
+    src.init(rs);
     const Selection sel = hist_phase<decltype(src), DT, SRC, kRowBlock, true>(src, P, 0, row, 0u, 1u, a_s, e, st, sm);
-    const PassEntry e1 = classify_phase<decltype(src), DT, SRC, kRowBlock, true>(src, P, 0, row, 0u, 1u, e, st, a_s, sm, 3u,
+    const PassEntry e1 = classify_phase<decltype(src), DT, SRC, kRowBlock, true>(src, P, 0, row, rs.k, 0u, 1u, e, st, a_s, sm, 3u,
                                                                                  sel, 1u, true);
-    finish_row<DT>(P, row, st, a_s, sm, 1, e1, HIST_IN_LDS, 3u);
+    finish_row<DT>(P, row, rs, st, a_s, sm, 1, e1, HIST_IN_LDS, 3u);
 }
 
 // The same for a row that fits one workgroup's registers (1024 lanes x 16 vectors x 16 bytes = 256 KiB):
@@ -1555,18 +1572,20 @@ __global__ void __launch_bounds__(kRowBlock) k_row_resident(Params P, bool only_
     typename Source::Tile t[kTiles];
     const int row = blockIdx.x;
     rtopk_row_trace* st = row_state(P, row);
+    const RowShape rs = row_shape<KeyOf<DT>::kBytes>(P, row);
     Source src;
-    src.init(P.keys, P.n, row);
+    src.init(rs);
     const u32 ntiles = src.ntiles();
 #ifdef RTOPK_TIMING
     unsigned long long tt[6];
     tt[4] = wall_clock64();
 #endif
-    const float drawn = init_row<DT>(P, row, st);
+    const float drawn = init_row<DT>(P, row, st, rs);
+    if (rs.k == 0) return;  // (ragged batches: an empty row, or nothing wanted from it)
     if (threadIdx.x == 0) sm.a_s = drawn;
     __syncthreads();
     const float a_s = sm.a_s;
-    const PassEntry e = pass_entry(P, st, 0);
+    const PassEntry e = pass_entry(P, st, 0, rs);
     auto arriving = [&](auto&& f) __attribute__((always_inline)) {
 #pragma unroll
         for (int c = 0; c < kAhead; ++c)
@@ -1581,12 +1600,12 @@ __global__ void __launch_bounds__(kRowBlock) k_row_resident(Params P, bool only_
 #ifdef RTOPK_TIMING
     tt[1] = wall_clock64();
 #endif
-    const PassEntry e1 = classify_phase<Source, DT, SRC, kRowBlock, true>(src, P, 0, row, 0u, 1u, e, st, a_s, sm, 3u, sel,
+    const PassEntry e1 = classify_phase<Source, DT, SRC, kRowBlock, true>(src, P, 0, row, rs.k, 0u, 1u, e, st, a_s, sm, 3u, sel,
                                                                           1u, true, resident);
 #ifdef RTOPK_TIMING
     tt[2] = wall_clock64();
 #endif
-    finish_row<DT>(P, row, st, a_s, sm, 1, e1, HIST_IN_LDS, 3u);
+    finish_row<DT>(P, row, rs, st, a_s, sm, 1, e1, HIST_IN_LDS, 3u);
 #ifdef RTOPK_TIMING
     tt[3] = wall_clock64();
     if (threadIdx.x == 0) {
@@ -1692,9 +1711,11 @@ __global__ void __launch_bounds__(kStreamBlock) __attribute__((amdgpu_waves_per_
     rtopk_row_trace* st = row_state(P, row);
     const u32 tid = threadIdx.x, lane = lane_id();
     RTOPK_STAMP(0);
-    init_row<DT>(P, row, st);
+    const RowShape rs = row_shape<KeyOf<DT>::kBytes>(P, row);
+    init_row<DT>(P, row, st, rs);
+    if (rs.k == 0) return;  // (ragged batches: an empty row, or nothing wanted from it)
     Source src;
-    src.init(P.keys, P.n, row);
+    src.init(rs);
     const u32 ntiles = src.ntiles();
     const DigitCtx ctx = make_digit_ctx(P, 0, 0.0f);
     const int nb = 1 << ctx.pi.bits;
@@ -1714,8 +1735,8 @@ __global__ void __launch_bounds__(kStreamBlock) __attribute__((amdgpu_waves_per_
     // elements will be set aside: keep that near 512), and enough to hold k elements
     constexpr u32 kTileElems = (u32)B * Source::kSlots;
     u32 t0 = (ntiles + 7u) / 8u;
-    const u32 by_k = (u32)(((u64)P.k * ntiles + 511u) / 512u);
-    const u32 need = ((u32)P.k + src.lead + kTileElems - 1u) / kTileElems;
+    const u32 by_k = (u32)(((u64)rs.k * ntiles + 511u) / 512u);
+    const u32 need = (rs.k + src.lead + kTileElems - 1u) / kTileElems;
     if (t0 < by_k) t0 = by_k;
     if (t0 < need) t0 = need;
     if (t0 > ntiles) t0 = ntiles;
@@ -1732,17 +1753,17 @@ __global__ void __launch_bounds__(kStreamBlock) __attribute__((amdgpu_waves_per_
     {
         // how many elements have been counted?  (tiles [0, t0) hold elements [0, t0 * tile - lead) of the row)
         const u64 seen64 = (u64)t0 * kTileElems - src.lead;
-        const u32 seen = seen64 < (u64)P.n ? (u32)seen64 : (u32)P.n;
+        const u32 seen = seen64 < (u64)rs.n ? (u32)seen64 : rs.n;
         bool distrust = false;
         Selection s0{};
-        if (seen >= (u32)P.k) s0 = select_from_counts<B>(counts, nb, (u32)P.k, sm, st, nothing, &distrust);
+        if (seen >= rs.k) s0 = select_from_counts<B>(counts, nb, rs.k, sm, st, nothing, &distrust);
         b0 = s0.bin;
         // the bound as a number: set aside what is not below the lower edge of bin b0 ("largest"), or what
         // is below its upper edge ("smallest": keys are complemented, bin b0 is raw bin maxd - b0)
         const u32 maxd = (u32)nb - 1u;
         const u64 Bo = largest ? b0 : maxd - b0;
         const u64 T = (largest ? Bo : Bo + 1u) << ctx.pi.shift;
-        if (seen < (u32)P.k) why = 2u;
+        if (seen < rs.k) why = 2u;
         else if (distrust) why = 1u;
         else if (!threshold_number<DT>(T, &thr)) why = 3u;
         // the part's own share of bins >= b0, scaled to the row, is what the sweep will set aside: give up now
@@ -1754,7 +1775,7 @@ __global__ void __launch_bounds__(kStreamBlock) __attribute__((amdgpu_waves_per_
         // ---- the sweep, in chunks of kStreamChunk tiles: the sweep notes the hits, then every lane fetches its own
         static_assert(Source::kSlots == 16, "one 16-bit mask per lane and tile");
         unsigned short* masks = (unsigned short*)sm.wide;  // [tile in chunk][lane]; the first part's histogram is done with
-        const char* row_bytes = (const char*)P.keys + (size_t)row * (size_t)P.n * KeyOf<DT>::kBytes;
+        const char* row_bytes = rs.x;
         for (u32 c0 = 0; c0 < ntiles; c0 += kStreamChunk) {
             const u32 c1 = c0 + kStreamChunk < ntiles ? c0 + kStreamChunk : ntiles;
             auto note = [&](const typename Source::Tile& cur, u32 bits) __attribute__((always_inline)) {
@@ -1824,7 +1845,7 @@ __global__ void __launch_bounds__(kStreamBlock) __attribute__((amdgpu_waves_per_
             atomicAdd(&sm.wide[digit_of<DT, SRC_KEY>(ctx.pi, e.x, e.y, ctx.dirmask, ctx.idx_max, 0.0f)], 1u);
         }
         __syncthreads();
-        sel = select_from_counts<B>(PlainCounts{sm.wide}, nb, (u32)P.k, sm, st,
+        sel = select_from_counts<B>(PlainCounts{sm.wide}, nb, rs.k, sm, st,
                                     [&]() __attribute__((always_inline)) {
                                         if (tid == 0) {
                                             sm.runW = 0;
@@ -1851,7 +1872,7 @@ __global__ void __launch_bounds__(kStreamBlock) __attribute__((amdgpu_waves_per_
         const u32 d = digit_of<DT, SRC_KEY>(ctx.pi, e.x, e.y, ctx.dirmask, ctx.idx_max, 0.0f);
         if ((int)d > bw) {
             const u32 pos = atomicAdd(&sm.runW, 1u);
-            if (pos < (u32)P.k) {
+            if (pos < rs.k) {
                 store_value<DT>(out_v, pos, e.x);
                 out_i[pos] = (long long)e.y;
             }
@@ -1860,7 +1881,7 @@ __global__ void __launch_bounds__(kStreamBlock) __attribute__((amdgpu_waves_per_
             if (pos < kStreamRank) sm.rank_list[pos] = e;
         }
     }
-    const PassEntry e0 = pass_entry(P, st, 0);
+    const PassEntry e0 = pass_entry(P, st, 0, rs);
     if (tid == 0) write_pass_record(st, 0, ctx.pi, e0, sel, 4u, 0u);
     if (sel.emit_all) return;
     __syncthreads();
@@ -1896,7 +1917,7 @@ __global__ void __launch_bounds__(kStreamBlock) __attribute__((amdgpu_waves_per_
             }
             if (i < C && rank < sel.k_inside) {
                 const u32 pos = sel.above + rank;
-                if (pos < (u32)P.k) {
+                if (pos < rs.k) {
                     store_value<DT>(out_v, pos, mine[r].x);
                     out_i[pos] = (long long)mine[r].y;
                 }
@@ -1937,7 +1958,7 @@ static rtopk_status launch_all(const Params& P, const Config& c, bool scaled, hi
         const long long cap = (long long)kRowBlock * kResidentVecs * (16 / KeyOf<DT>::kBytes);
         // (a row that does not start on a 16-byte boundary has up to E - 1 lead-in elements in its first vector)
         constexpr int kE = 16 / KeyOf<DT>::kBytes;
-        const bool aligned = (uintptr_t)P.keys % 16 == 0 && (batch == 1 || P.n % kE == 0);
+        const bool aligned = (uintptr_t)P.keys % 16 == 0 && (batch == 1 || P.n % kE == 0) && !P.row_offsets;
         const bool resident = P.n + (aligned ? 0 : kE - 1) <= cap;
         // small k, unscaled: the one-sweep kernel first; the two-sweep kernel then takes the rows it marked
         const bool one_sweep = c.one_sweep && !scaled;

@@ -44,10 +44,12 @@ __global__ void __launch_bounds__(kRowBlock) k_sort_small(Params P) {
     constexpr int B = kRowBlock;
     const int row = blockIdx.x;
     const u32 tid = threadIdx.x;
-    const u32 k = (u32)P.k;
+    const RowShape rs = row_shape<KeyOf<DT>::kBytes>(P, row);
+    const u32 k = rs.k;
+    if (k == 0) return;
     char* out_v = (char*)P.out_values + (size_t)row * (size_t)P.k * KeyOf<DT>::kBytes;
     long long* out_i = P.out_indices + (size_t)row * (size_t)P.k;
-    const char* x = (const char*)P.keys + (size_t)row * (size_t)P.n * KeyOf<DT>::kBytes;
+    const char* x = rs.x;
     u32 m = 64;
     while (m < k) m <<= 1;
     for (u32 i = tid; i < m; i += B)
@@ -81,8 +83,7 @@ __device__ __forceinline__ u64* sort_buffer(const Params& P, u32 which, int row)
     return (u64*)(P.cand[which] + (size_t)row * P.cand_stride);
 }
 // the chunk of workgroup w: [begin, end), a whole number of kSortBlock-element tiles but for the row's end
-__device__ __forceinline__ void sort_chunk(const Params& P, u32 w, u32& begin, u32& end) {
-    const u32 k = (u32)P.k;
+__device__ __forceinline__ void sort_chunk(const Params& P, u32 k, u32 w, u32& begin, u32& end) {
     u32 per = (k + (u32)P.Gs - 1u) / (u32)P.Gs;
     per = (per + kSortBlock - 1u) / kSortBlock * kSortBlock;
     const u64 b = (u64)w * per, e = b + per;
@@ -94,11 +95,12 @@ __device__ __forceinline__ void sort_chunk(const Params& P, u32 w, u32& begin, u
 template <int DT>
 __global__ void __launch_bounds__(kSortBlock) k_sort_pack(Params P) {
     const int row = blockIdx.y;
+    const u32 row_k = row_shape<KeyOf<DT>::kBytes>(P, row).k;
     const char* out_v = (const char*)P.out_values + (size_t)row * (size_t)P.k * KeyOf<DT>::kBytes;
     const long long* out_i = P.out_indices + (size_t)row * (size_t)P.k;
     u64* dst = sort_buffer(P, 0u, row);
     u32 begin, end;
-    sort_chunk(P, blockIdx.x, begin, end);
+    sort_chunk(P, row_k, blockIdx.x, begin, end);
     for (u32 i = begin + threadIdx.x; i < end; i += kSortBlock)
         dst[i] = sort_key_of<DT>(load_value<DT>(out_v, i), (u32)out_i[i], P.dirmask);
     if (blockIdx.x == 0 && threadIdx.x < sizeof(SortState) / 4) ((u32*)sort_state(P, row))[threadIdx.x] = 0;
@@ -109,11 +111,12 @@ template <int DT>
 __global__ void __launch_bounds__(kSortBlock) k_sort_hist(Params P, int j) {
     __shared__ u32 h[kSortBins];
     const int row = blockIdx.y;
+    const u32 row_k = row_shape<KeyOf<DT>::kBytes>(P, row).k;
     const u64* src = sort_buffer(P, sort_state(P, row)->cur[j], row);
     if (threadIdx.x < kSortBins) h[threadIdx.x] = 0;
     __syncthreads();
     u32 begin, end;
-    sort_chunk(P, blockIdx.x, begin, end);
+    sort_chunk(P, row_k, blockIdx.x, begin, end);
     for (u32 i = begin + threadIdx.x; i < end; i += kSortBlock) atomicAdd(&h[(u32)(src[i] >> (8 * j)) & 255u], 1u);
     __syncthreads();
     u32* table = P.sort_hist + (size_t)row * kSortBins * P.Gs;
@@ -127,6 +130,7 @@ __global__ void __launch_bounds__(kRowBlock) k_sort_scan(Params P, int j) {
     __shared__ u32 carry, all_in_one;
     const int row = blockIdx.x;
     const u32 tid = threadIdx.x;
+    const u32 row_k = row_shape<KeyOf<DT>::kBytes>(P, row).k;
     u32* table = P.sort_hist + (size_t)row * kSortBins * P.Gs;
     const u32 total = (u32)kSortBins * (u32)P.Gs;
     if (tid == 0) {
@@ -138,7 +142,7 @@ __global__ void __launch_bounds__(kRowBlock) k_sort_scan(Params P, int j) {
     if (tid < kSortBins) {
         u32 s = 0;
         for (int w = 0; w < P.Gs; ++w) s += table[(size_t)tid * P.Gs + w];
-        if (s == (u32)P.k) all_in_one = 1;
+        if (s == row_k) all_in_one = 1;  // (also a row with nothing to sort: every count is 0)
     }
     __syncthreads();
     const bool skip = all_in_one != 0;
@@ -168,6 +172,7 @@ __global__ void __launch_bounds__(kSortBlock) k_sort_scatter(Params P, int j) {
     __shared__ u32 base[kSortBins];          // next free position of every bin for this workgroup
     __shared__ u32 wcount[W][kSortBins];     // per wave: elements of each bin in the current tile; then their offset
     const int row = blockIdx.y;
+    const u32 row_k = row_shape<KeyOf<DT>::kBytes>(P, row).k;
     const SortState* st = sort_state(P, row);
     if (st->skip[j]) return;
     const u32 tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
@@ -176,7 +181,7 @@ __global__ void __launch_bounds__(kSortBlock) k_sort_scatter(Params P, int j) {
     const u32* table = P.sort_hist + (size_t)row * kSortBins * P.Gs;
     if (tid < kSortBins) base[tid] = table[(size_t)tid * P.Gs + blockIdx.x];
     u32 begin, end;
-    sort_chunk(P, blockIdx.x, begin, end);
+    sort_chunk(P, row_k, blockIdx.x, begin, end);
     for (u32 t0 = begin; t0 < end; t0 += kSortBlock) {
         for (u32 q = tid; q < (u32)(W * kSortBins); q += kSortBlock) (&wcount[0][0])[q] = 0;
         __syncthreads();
@@ -216,12 +221,14 @@ __global__ void __launch_bounds__(kSortBlock) k_sort_scatter(Params P, int j) {
 template <int DT>
 __global__ void __launch_bounds__(kSortBlock) k_sort_unpack(Params P) {
     const int row = blockIdx.y;
+    const RowShape rs = row_shape<KeyOf<DT>::kBytes>(P, row);
+    const u32 row_k = rs.k;
     const u64* src = sort_buffer(P, sort_state(P, row)->cur[kSortPasses], row);
     char* out_v = (char*)P.out_values + (size_t)row * (size_t)P.k * KeyOf<DT>::kBytes;
     long long* out_i = P.out_indices + (size_t)row * (size_t)P.k;
-    const char* x = (const char*)P.keys + (size_t)row * (size_t)P.n * KeyOf<DT>::kBytes;
+    const char* x = rs.x;
     u32 begin, end;
-    sort_chunk(P, blockIdx.x, begin, end);
+    sort_chunk(P, row_k, blockIdx.x, begin, end);
     for (u32 i = begin + threadIdx.x; i < end; i += kSortBlock) {
         const u32 idx = (u32)src[i];
         out_i[i] = (long long)idx;
