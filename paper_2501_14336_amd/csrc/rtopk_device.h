@@ -153,7 +153,7 @@ __device__ __forceinline__ u32 digit_of(const PassInfo pi, u32 raw, u32 idx, u32
         float y = __uint_as_float(raw) - a_s;
         u = KeyOf<RTOPK_F32>::key(__float_as_uint(y)) ^ dirmask;
     }
-    return (u >> pi.shift) & ((1u << pi.bits) - 1u);
+    return (u >> pi.shift) & (pi.bits >= 32u ? 0xffffffffu : (1u << pi.bits) - 1u);
 }
 
 // Everything a kernel needs to turn elements into digits of one pass, as wave-uniform scalars.
@@ -300,6 +300,18 @@ struct KeySource {
             }
         }
     }
+    // Digits of the E elements of vector u for ANY pass (source and window chosen at run time): the sweeps over X
+    // that come after an in-place pass.
+    template <int DT2>
+    __device__ __forceinline__ void digits_of_pass(const Tile& t, int u, const DigitCtx& c, u32 (&dg)[E]) const {
+#pragma unroll
+        for (int j = 0; j < E; ++j) {
+            u32 raw, idx;
+            bool valid;
+            get(t, u * E + j, raw, idx, valid);
+            dg[j] = digit_of<DT2, SRC_RUNTIME>(c.pi, raw, idx, c.dirmask, c.idx_max, c.a_s);
+        }
+    }
     // Element s of the tile as an fp32 number that orders like the element (exact widening for
     // 16-bit types; x - a_s under scaling).  NaN stays NaN.
     template <int SRC>
@@ -388,7 +400,7 @@ struct CandSource {
     }
     // Digits of the two elements of vector u for any pass (source chosen at run time).
     template <int DT>
-    __device__ __forceinline__ void digits(const Tile& t, int u, const DigitCtx& c, u32 (&dg)[E]) const {
+    __device__ __forceinline__ void digits_of_pass(const Tile& t, int u, const DigitCtx& c, u32 (&dg)[E]) const {
         dg[0] = digit_of<DT, SRC_RUNTIME>(c.pi, t.r[u].x, t.r[u].y, c.dirmask, c.idx_max, c.a_s);
         dg[1] = digit_of<DT, SRC_RUNTIME>(c.pi, t.r[u].z, t.r[u].w, c.dirmask, c.idx_max, c.a_s);
     }

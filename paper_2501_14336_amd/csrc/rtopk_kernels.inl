@@ -98,10 +98,20 @@ struct PassEntry {
     bool prev_multi; // the previous pass was run by the many-workgroup kernels
     bool in_lds;     // the candidates are in the workgroup's LDS list (few of them), not in the candidate array
     u32 src_array;   // which of the two candidate arrays holds them (meaningless for pass 0 over X)
+    bool src_in_x;   // they were never copied: they are the elements of X that match the passes so far
+    u32 chain;       // how many passes directly before this one left their candidates in place (see in-place passes)
 };
 // Which candidate array a pass wrote is part of its record (bit 24 of `window`): a pass that reads array a writes
 // array 1 - a, a pass over X writes array 0, the prefilter sweep writes array 1.
 constexpr u32 kWindowArrayBit = 24;
+// In-place passes.  A pass whose chosen bin holds at least 7/8 of its candidates (keys crowded into a narrow range,
+// many duplicates: Section 4.2) does not copy them: it only sends its few winners to the output and counts the next
+// digit of the elements in the bin.  The next pass then reads the same source (X itself, or the candidate array of
+// the last pass that did copy) and tells candidates from the rest by the digits of all the in-place passes before it,
+// read as one wide digit together with its own; once the key's digits are used up that way, the index digits go on
+// with "key equals the pivot's" as the condition.  Bits 25 and 26 of a record's `window`: the pass left its
+// candidates in place; in place in X.
+constexpr u32 kWindowInPlaceBit = 25, kWindowInXBit = 26;
 
 // Few enough candidates are ranked directly against each other (one per lane) instead of walking the
 // remaining digits; the list lives where the LDS histogram is, which no longer has a use then.
@@ -118,6 +128,8 @@ __device__ __forceinline__ PassEntry pass_entry(const Params& P, const rtopk_row
         e.prev_multi = true;
         e.in_lds = false;
         e.src_array = 1;  // (what a prefilter sweep kept)
+        e.src_in_x = false;
+        e.chain = 0;
     } else {
         e.cand = st->pass_rec[p - 1].cand_after;
         e.k_rem = st->pass_rec[p - 1].k_after;
@@ -126,6 +138,9 @@ __device__ __forceinline__ PassEntry pass_entry(const Params& P, const rtopk_row
         e.prev_multi = st->pass_rec[p - 1].where == 1u;
         e.in_lds = false;
         e.src_array = (st->pass_rec[p - 1].window >> kWindowArrayBit) & 1u;
+        e.src_in_x = ((st->pass_rec[p - 1].window >> kWindowInXBit) & 1u) != 0;
+        e.chain = 0;
+        for (int q = p - 1; q >= 0 && ((st->pass_rec[q].window >> kWindowInPlaceBit) & 1u); --q) ++e.chain;
     }
     return e;
 }
@@ -242,7 +257,8 @@ __device__ __forceinline__ u32* seg_records(const Params& P, u32 a, int row) {
 }
 
 __device__ __forceinline__ void write_pass_record(rtopk_row_trace* st, int p, const PassInfo pi, const PassEntry& e,
-                                                  const Selection& sel, u32 where, u32 out_array) {
+                                                  const Selection& sel, u32 where, u32 out_array, bool in_place = false,
+                                                  bool in_x = false) {
     // one thread; every field is written exactly once per call
     st->pass_rec[p].bin = sel.bin;
     st->pass_rec[p].k_after = sel.emit_all ? 0u : sel.k_inside;
@@ -250,7 +266,8 @@ __device__ __forceinline__ void write_pass_record(rtopk_row_trace* st, int p, co
     st->pass_rec[p].winners = sel.above + (sel.emit_all ? sel.inside : 0u);
     st->pass_rec[p].out_before = e.out_before;
     st->pass_rec[p].cand_before = e.cand;
-    st->pass_rec[p].window = pi.src | (pi.shift << 8) | (pi.bits << 16) | (out_array << kWindowArrayBit);
+    st->pass_rec[p].window = pi.src | (pi.shift << 8) | (pi.bits << 16) | (out_array << kWindowArrayBit) |
+                             ((in_place ? 1u : 0u) << kWindowInPlaceBit) | ((in_x ? 1u : 0u) << kWindowInXBit);
     st->pass_rec[p].where = where;
 }
 
@@ -265,7 +282,7 @@ template <int DT, int SRC, class Source>
 __device__ __forceinline__ void vector_digits(const Source& src, const typename Source::Tile& t, int u,
                                               const DigitCtx& c, u32 (&dg)[Source::E]) {
     if constexpr (SRC == SRC_RUNTIME)
-        src.template digits<DT>(t, u, c, dg);
+        src.template digits_of_pass<DT>(t, u, c, dg);
     else
         src.template digits<SRC>(t, u, c, dg);
 }
@@ -441,8 +458,8 @@ __device__ __forceinline__ Selection hist_phase(const Source& src, const Params&
         } else {
             for_each_tile<1>(
                 src, wg, G, ntiles,
-                [&](const typename Source::Tile& cur) { hist_tile_raw<true, Source>(src, cur, ctx, hs); },
-                [&](const typename Source::Tile& cur) { hist_tile_raw<false, Source>(src, cur, ctx, hs); });
+                [&](const typename Source::Tile& cur) __attribute__((always_inline)) { hist_tile_raw<true, Source>(src, cur, ctx, hs); },
+                [&](const typename Source::Tile& cur) __attribute__((always_inline)) { hist_tile_raw<false, Source>(src, cur, ctx, hs); });
         }
         __syncthreads();
         RTOPK_STAMP(6);
@@ -473,13 +490,13 @@ __device__ __forceinline__ Selection hist_phase(const Source& src, const Params&
                 hist_tile<true, false, Source, DT, SRC>(src, cur, ctx, hs, lane);
         });
     } else {
-        auto full = [&](const typename Source::Tile& cur) {
+        auto full = [&](const typename Source::Tile& cur) __attribute__((always_inline)) {
             if (hot_lanes<Source, DT, SRC>(src, cur, ctx) >= 12u)  // wave-uniform
                 hist_tile<true, true, Source, DT, SRC>(src, cur, ctx, hs, lane);
             else
                 hist_tile<true, false, Source, DT, SRC>(src, cur, ctx, hs, lane);
         };
-        auto edge = [&](const typename Source::Tile& cur) {
+        auto edge = [&](const typename Source::Tile& cur) __attribute__((always_inline)) {
             hist_tile<false, true, Source, DT, SRC>(src, cur, ctx, hs, lane);
         };
         if (!SINGLE && P.pre_stride != 0) {
@@ -556,6 +573,10 @@ struct ClassifyOut {
     // a window of several passes' digits (see classify_phase, MERGED).
     u32 wmin, wmax;
     u32 b;
+    // after in-place passes over all of the key's digits: the index digits' candidates are the elements whose ordered
+    // key (direction applied) is the pivot's
+    bool need_key_eq;
+    u32 key_eq;
     // float mode (first pass over X only): the same two tests as comparisons of the element itself with the
     // numbers whose keys are the bin's boundaries:  win = (x < t1) ^ flip,  at-least-candidate = (x < t2) ^ flip
     float t1, t2;
@@ -614,6 +635,14 @@ __device__ __forceinline__ void slot_masks(const Source& src, const typename Sou
         } else {
             mw = ballot64(d >= o.wmin && d <= o.wmax) & vm;
             mc = ballot64(d == o.b) & vm & ~mw;
+            if (o.need_key_eq) {
+                u32 raw, idx;
+                bool v2;
+                src.get(t, s, raw, idx, v2);
+                const u64 ok = ballot64((KeyOf<DT>::key(raw) ^ c.dirmask) == o.key_eq);
+                mw &= ok;
+                mc &= ok;
+            }
         }
     }
 }
@@ -840,6 +869,66 @@ __device__ __forceinline__ void classify_tile(const Source& src, const typename 
     }
 }
 
+// One tile of an in-place pass (see in-place passes): nearly every element read is a candidate and stays where it
+// is; its next digit is counted (lanes that share the first lane's digit with one LDS add -- the crowd these passes
+// exist for usually shares it), the few winners are staged as usual.  OWN / NEXT: what this pass's digit and the next
+// one's are taken from, fixed at compile time so that the slot loop holds no decisions: both from the key, both from
+// the scaled key, both from the index, or the key's last digit followed by the index's first.  KEY_EQ (index digits
+// after in-place key digits): only elements with the pivot's key count at all.
+template <bool FULL, int OWN, int NEXT, bool KEY_EQ, class Source, int DT, int B, int ST>
+__device__ __forceinline__ void inplace_tile(const Source& src, const typename Source::Tile& t, const DigitCtx& c,
+                                             const ClassifyOut<DT>& o, Shared<B, ST>& sm, u32 lane, u32 wave, WriteState& ws,
+                                             const NextCount& nc) {
+    constexpr int S = Source::kSlots;
+    uint2* st = sm.stage[wave];
+    const u64 me_bit = 1ull << lane;
+    const u32 wmask = c.pi.bits >= 32u ? 0xffffffffu : (1u << c.pi.bits) - 1u;
+    const u32 nmask = (1u << nc.pi.bits) - 1u;
+#pragma unroll
+    for (int s = 0; s < S; ++s) {
+        if (s % kStageGroup == 0) make_room<DT, false>(o, sm, lane, wave, ws, nc);  // (winners are few: a call will do)
+        u32 raw, idx;
+        bool valid;
+        src.get(t, s, raw, idx, valid);
+        u32 u;  // the 32 bits this pass's digit is a window of
+        if (OWN == SRC_IDX)
+            u = c.idx_max - idx;
+        else if (OWN == SRC_KEY)
+            u = KeyOf<DT>::key(raw) ^ c.dirmask;
+        else
+            u = KeyOf<RTOPK_F32>::key(__float_as_uint(__uint_as_float(raw) - c.a_s)) ^ c.dirmask;
+        const u32 wd = (u >> c.pi.shift) & wmask;
+        bool ok = FULL || valid;
+        if (KEY_EQ) ok = ok && (KeyOf<DT>::key(raw) ^ c.dirmask) == o.key_eq;
+        const u64 mw = ballot64(ok && wd >= o.wmin && wd <= o.wmax);
+        const u64 mc = ballot64(ok && wd == o.b);
+        if (mc & me_bit) {
+            const u32 v = NEXT == OWN ? u : c.idx_max - idx;
+            hist_add(nc.hist, (v >> nc.pi.shift) & nmask, lane);
+        }
+        if (mw) {
+            if (mw & me_bit) st[ws.fillW + mbcnt64(mw)] = make_uint2(raw, idx);
+            ws.fillW += (u32)__popcll(mw);
+        }
+    }
+}
+// ... with OWN / NEXT / KEY_EQ taken from the pass at run time, once per tile.
+template <bool FULL, class Source, int DT, int B, int ST>
+__device__ __forceinline__ void inplace_tile_any(const Source& src, const typename Source::Tile& t, const DigitCtx& c,
+                                                 const ClassifyOut<DT>& o, Shared<B, ST>& sm, u32 lane, u32 wave,
+                                                 WriteState& ws, const NextCount& nc) {
+    if (c.pi.src == SRC_KEY && nc.pi.src == SRC_KEY)
+        inplace_tile<FULL, SRC_KEY, SRC_KEY, false>(src, t, c, o, sm, lane, wave, ws, nc);
+    else if (c.pi.src == SRC_KEY)
+        inplace_tile<FULL, SRC_KEY, SRC_IDX, false>(src, t, c, o, sm, lane, wave, ws, nc);
+    else if (c.pi.src == SRC_IDX && o.need_key_eq)
+        inplace_tile<FULL, SRC_IDX, SRC_IDX, true>(src, t, c, o, sm, lane, wave, ws, nc);
+    else if (c.pi.src == SRC_IDX)
+        inplace_tile<FULL, SRC_IDX, SRC_IDX, false>(src, t, c, o, sm, lane, wave, ws, nc);
+    else if constexpr (DT == RTOPK_F32)
+        inplace_tile<FULL, SRC_SCALED, SRC_SCALED, false>(src, t, c, o, sm, lane, wave, ws, nc);
+}
+
 // One tile of the prefilter sweep over fp32 keys, the cheap way.  countBin needs only the element's raw top bits
 // (hist_tile_raw: the bins are renamed afterwards), and "digit >= bound" is one float comparison with the number at
 // the bound's edge (o.t2), so the straight path is a shift, an LDS add and a compare per element.  The comparison
@@ -912,11 +1001,40 @@ __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Par
     DigitCtx ctx = make_digit_ctx(P, p, a_s);
     const PassInfo own_pi = ctx.pi;
     if (sel0) ctx.pi.bits += P.pass[p - 1].bits;  // the digit window of both passes
+    // In-place passes before this one: their digits, read as one wide digit with this pass's own, tell this pass's
+    // candidates from the rest of what it reads.  (Index digits after in-place key digits: the key must be the pivot's.)
+    u32 prefix = sel0 ? sel0->bin : 0u;
+    bool need_key_eq = false;
+    u32 key_eq = 0;
+    if (!PRE && !sel0 && e.chain != 0) {
+        int q = p - 1;
+        u32 sh = 0;
+        for (; q >= p - (int)e.chain && P.pass[q].src == own_pi.src; --q) {
+            prefix |= st->pass_rec[q].bin << sh;
+            sh += P.pass[q].bits;
+        }
+        ctx.pi.bits += sh;
+        if (q >= p - (int)e.chain) {
+            // the chain goes on into the key's digits: every one of them belongs to the pivot's key
+            need_key_eq = true;
+            for (int z = 0; z < p; ++z)
+                if (P.pass[z].src == SRC_KEY) key_eq |= st->pass_rec[z].bin << P.pass[z].shift;
+        }
+    }
     const int nb = 1 << own_pi.bits;
     const u32 tid = threadIdx.x;
     const u32 lane = lane_id();
     const u32 wave = tid >> 6;
     const u32 ntiles = src.ntiles();
+    // Leave the candidates where they are?  (Many workgroups per row only; see in-place passes.)
+    bool inplace = false;
+    if (!SINGLE && !PRE && !sel0 && !sel.emit_all && p + 1 < P.npass && sel.inside > P.small &&
+        (u64)sel.inside * 8u > (u64)e.cand * 7u) {
+        const PassInfo nx = P.pass[p + 1];
+        const bool same = nx.src == own_pi.src && ctx.pi.bits + nx.bits <= 32u;    // the next digit extends this window
+        const bool into_index = own_pi.src == SRC_KEY && nx.src == SRC_IDX;        // the key's last digit
+        inplace = same || into_index;
+    }
 
 #ifdef RTOPK_TIMING
     unsigned long long t_begin = wall_clock64(), t_pro = 0, t_sweep = 0;
@@ -925,6 +1043,8 @@ __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Par
     // which candidate array this pass writes: the other one than it reads; array 0 from X; a prefilter sweep array 1
     const bool from_x = !std::is_same<Source, CandSource<B, kVecs>>::value;
     const u32 out_array = PRE ? 1u : from_x ? 0u : 1u - e.src_array;
+    const u32 rec_array = inplace ? e.src_array : out_array;
+    const bool rec_inplace = inplace, rec_in_x = inplace && (from_x || e.src_in_x);
     if constexpr (PRE) {
         // this workgroup's segment starts where the tiles of the workgroups before it would end if every element
         // of theirs were kept (tiles are dealt round-robin: workgroup v has ntiles / G of them, one more if
@@ -969,7 +1089,7 @@ __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Par
             st->pass_rec[0].cand_before = st->pre_kept;
             st->pre_merged = 1u;
         }
-        write_pass_record(st, p, own_pi, e, sel, where, out_array);
+        write_pass_record(st, p, own_pi, e, sel, where, rec_array, rec_inplace, rec_in_x);
         // after a prefilter the first digit pass looks at what the prefilter kept, not at all of X
         if (!SINGLE && SRC == SRC_RUNTIME && p == 0) st->pass_rec[0].cand_before = st->pre_kept;  // after a prefilter
     }
@@ -993,11 +1113,15 @@ __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Par
     o.cand_lds = to_rank ? (uint2*)sm.hist : nullptr;
     o.kk = row_k;
     o.ncap = (u32)P.cand_stride;
-    // (with sel0: the window holds pass p - 1's digit above pass p's own)
-    o.b = sel0 ? (sel0->bin << own_pi.bits) | sel.bin : sel.bin;
-    o.wmax = ctx.pi.bits >= 32u ? 0xffffffffu : (1u << ctx.pi.bits) - 1u;
+    // The window holds the digits of earlier passes above pass p's own: of the in-place passes before it (whatever
+    // differs from them there is no candidate of this pass: neither winner nor kept), or, with sel0, pass p - 1's
+    // (whatever is better there is a winner of that pass, emitted here).
+    o.b = (prefix << own_pi.bits) | sel.bin;
+    o.wmax = sel0 ? (ctx.pi.bits >= 32u ? 0xffffffffu : (1u << ctx.pi.bits) - 1u) : (prefix << own_pi.bits) | ((1u << own_pi.bits) - 1u);
     o.wmin = sel.emit_all ? o.b : o.b + 1u;
     if (!sel.emit_all && o.b == o.wmax) { o.wmin = 1u; o.wmax = 0u; }  // the top bin: nothing lies above it
+    o.need_key_eq = need_key_eq;
+    o.key_eq = key_eq;
     // First pass over X: the digit is the key's top bits, so "digit > b" and "digit >= b" are comparisons of
     // the element with two numbers -- two instructions per element instead of the whole key transform.
     bool floatcmp = false;
@@ -1007,6 +1131,7 @@ __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Par
         const bool largest = P.dirmask == 0;
         const u32 maxd = (1u << ctx.pi.bits) - 1u;
         const u64 Bo = largest ? sel.bin : maxd - sel.bin;  // the chosen bin in the uncomplemented key domain
+        // (only the very first pass over X gets here: no digits of earlier passes above this one's)
         const u64 Ta = Bo << ctx.pi.shift, Tb = (Bo + 1) << ctx.pi.shift;
         float ta, tb;
         if (threshold_number<DT>(Ta, &ta) && threshold_number<DT>(Tb, &tb)) {
@@ -1092,9 +1217,11 @@ __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Par
     // tiles of X are dealt round-robin to the row's workgroups; a candidate segment belongs to one workgroup
     // (one tile prefetched while one is processed; the sweeps that write into the stream of reads measured faster
     // that way than with two)
-    for_each_tile<SINGLE || PRE ? 1 : 2>(
+    // (the tile code is expanded at each of its few places in the pipeline: called, it would find everything it needs
+    // in memory, and a call first waits for all the wave's outstanding loads)
+    for_each_tile<1>(
         src, own_segment ? 0u : wg, own_segment ? 1u : G, ntiles,
-        [&](const typename Source::Tile& cur) {
+        [&](const typename Source::Tile& cur) __attribute__((always_inline)) {
             if constexpr (PRE && DT == RTOPK_F32 && SRC == SRC_KEY) {
                 if (raw_pre) {
                     const bool hot = hot_lanes<Source, DT, SRC>(src, cur, ctx) >= 12u;
@@ -1115,19 +1242,37 @@ __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Par
                 else
                     classify_tile<true, false, Source, DT, SRC, B, false, true, false>(src, cur, ctx, o, sm, lane, wave, ws, nc);
             } else if constexpr (SRC != SRC_RUNTIME) {
+                if constexpr (!SINGLE) {
+                    if (inplace) {
+                        inplace_tile_any<true>(src, cur, ctx, o, sm, lane, wave, ws, nc);
+                        return;
+                    }
+                }
                 if (floatcmp)
                     classify_tile<true, true, Source, DT, SRC, B, false, false>(src, cur, ctx, o, sm, lane, wave, ws, nc);
                 else
                     classify_tile<true, false, Source, DT, SRC, B, false, false>(src, cur, ctx, o, sm, lane, wave, ws, nc);
             } else {
+                if constexpr (!SINGLE) {
+                    if (inplace) {
+                        inplace_tile_any<true>(src, cur, ctx, o, sm, lane, wave, ws, nc);
+                        return;
+                    }
+                }
                 classify_tile<true, false, Source, DT, SRC, B>(src, cur, ctx, o, sm, lane, wave, ws, nc);
             }
         },
-        [&](const typename Source::Tile& cur) {
+        [&](const typename Source::Tile& cur) __attribute__((always_inline)) {
             if constexpr (PRE && DT == RTOPK_F32 && SRC == SRC_KEY) {
                 if (raw_pre) {
                     if (P.dirmask == 0) prefilter_tile_raw<false, true, true, Source>(src, cur, ctx, o, sm, lane, wave, ws, nc);
                     else prefilter_tile_raw<false, true, false, Source>(src, cur, ctx, o, sm, lane, wave, ws, nc);
+                    return;
+                }
+            }
+            if constexpr (!SINGLE && !PRE) {
+                if (inplace) {
+                    inplace_tile_any<false>(src, cur, ctx, o, sm, lane, wave, ws, nc);
                     return;
                 }
             }
@@ -1177,9 +1322,11 @@ __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Par
             for (int j = tid; j < nb_next; j += B) mine[j] = sm.hist[j];
             if (tid == 0) {
                 mine[nb_next] = 0;
-                u32* seg = seg_records(P, out_array, row) + (size_t)wg * 2;
-                seg[0] = runC;
-                seg[1] = PRE ? sm.runC - runC : myC;  // (the prefilter learns its count by writing)
+                if (!inplace) {  // (in place: the segments are those of the pass that wrote the array, or there are none: X)
+                    u32* seg = seg_records(P, out_array, row) + (size_t)wg * 2;
+                    seg[0] = runC;
+                    seg[1] = PRE ? sm.runC - runC : myC;  // (the prefilter learns its count by writing)
+                }
                 if (PRE) atomicAdd(&st->pre_kept, sm.runC - runC);
             }
         }
@@ -1212,7 +1359,9 @@ __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Par
     next.finished = sel.emit_all;
     next.prev_multi = !SINGLE;
     next.in_lds = to_rank;
-    next.src_array = out_array;
+    next.src_array = inplace ? e.src_array : out_array;
+    next.src_in_x = inplace && (from_x || e.src_in_x);
+    next.chain = inplace ? e.chain + 1u : 0u;
     return next;
 }
 
@@ -1365,6 +1514,8 @@ __global__ void __launch_bounds__(kGridBlock) k_pass0_after_prefilter(Params P) 
             e1.prev_multi = true;
             e1.in_lds = false;
             e1.src_array = 1u;
+            e1.src_in_x = false;
+            e1.chain = 0;
             __syncthreads();  // everybody has read the first selectBin's result: its LDS words may be reused
             const Selection sel1 = select_pass<kGridBlock>(PlainCounts{hist_buffer(P, kHistSecond, row)}, 1 << P.pass[1].bits,
                                                            e1, sm, st);
@@ -1385,8 +1536,9 @@ __global__ void __launch_bounds__(kGridBlock) k_pass0_after_prefilter(Params P) 
     }
 }
 
-// Pass p >= 1 on the grid: workgroup w classifies the candidates workgroup w kept in the sweep before.
-template <int DT>
+// Pass p >= 1 on the grid: workgroup w classifies the candidates workgroup w kept in the sweep before -- or, after
+// in-place passes that began with the first, its tiles of X once more.
+template <int DT, bool NT>
 __global__ void __launch_bounds__(kGridBlock) k_classify_cand(Params P, int p) {
     __shared__ Shared<kGridBlock> sm;
     const int row = blockIdx.y;
@@ -1398,13 +1550,22 @@ __global__ void __launch_bounds__(kGridBlock) k_classify_cand(Params P, int p) {
     if (p == 1 && st->pre_merged != 0u) return;
     const PassEntry e = pass_entry(P, st, p, rs);
     if (!multi_runs_pass(P, e, p)) return;
-    const u32* seg = seg_records(P, e.src_array, row) + (size_t)blockIdx.x * 2;
-    CandSource<kGridBlock, kVecs> src;
-    src.init(P.cand[e.src_array] + (size_t)row * P.cand_stride, seg[0], seg[1], (u32)P.cand_stride);
-    // its own tiles only: the segment is this workgroup's alone
     const Selection sel = select_pass<kGridBlock>(PlainCounts{global_hist(P, p, row)}, 1 << P.pass[p].bits, e, sm, st);
-    classify_phase<decltype(src), DT, SRC_RUNTIME, kGridBlock, false>(src, P, p, row, rs.k, blockIdx.x, gridDim.x, e, st, st->a_s,
-                                                                      sm, 1u, sel, gridDim.x, true);
+    if (e.src_in_x) {
+        KeySource<DT, kGridBlock, key_vecs<DT>(), NT> src;
+        src.init(rs);
+        const u32 ntiles = src.ntiles();
+        classify_phase<decltype(src), DT, SRC_RUNTIME, kGridBlock, false>(src, P, p, row, rs.k, blockIdx.x, gridDim.x, e, st,
+                                                                          st->a_s, sm, 1u, sel,
+                                                                          ntiles < gridDim.x ? ntiles : gridDim.x, false);
+    } else {
+        const u32* seg = seg_records(P, e.src_array, row) + (size_t)blockIdx.x * 2;
+        CandSource<kGridBlock, kVecs> src;
+        src.init(P.cand[e.src_array] + (size_t)row * P.cand_stride, seg[0], seg[1], (u32)P.cand_stride);
+        // its own tiles only: the segment is this workgroup's alone
+        classify_phase<decltype(src), DT, SRC_RUNTIME, kGridBlock, false>(src, P, p, row, rs.k, blockIdx.x, gridDim.x, e, st,
+                                                                          st->a_s, sm, 1u, sel, gridDim.x, true);
+    }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1507,6 +1668,10 @@ __global__ void __launch_bounds__(kRowBlock) k_finish(Params P) {
     while (p < P.npass && st->pass_rec[p].where != 0u) ++p;  // first pass the grid kernels left undone
     if (p == P.npass) return;
     const PassEntry e = pass_entry(P, st, p, rs);
+    if (e.src_in_x) {  // never expected: a pass that leaves its candidates in X leaves more than this kernel takes
+        if (threadIdx.x == 0) st->error |= 16u;
+        return;
+    }
     finish_row<DT>(P, row, rs, st, st->a_s, sm, p, e, HIST_IN_GLOBAL, 2u);  // its histogram was published by the pass before it
 }
 
@@ -1743,8 +1908,8 @@ __global__ void __launch_bounds__(kStreamBlock) __attribute__((amdgpu_waves_per_
     auto nothing = []() __attribute__((always_inline)) {};
     for_each_tile<2>(
         src, 0u, 1u, ntiles,
-        [&](const typename Source::Tile& cur) { hist_tile_raw<true, Source>(src, cur, ctx, hs); },
-        [&](const typename Source::Tile& cur) { hist_tile_raw<false, Source>(src, cur, ctx, hs); }, 0u, t0);
+        [&](const typename Source::Tile& cur) __attribute__((always_inline)) { hist_tile_raw<true, Source>(src, cur, ctx, hs); },
+        [&](const typename Source::Tile& cur) __attribute__((always_inline)) { hist_tile_raw<false, Source>(src, cur, ctx, hs); }, 0u, t0);
     __syncthreads();
     RTOPK_STAMP(1);
     u32 why = 0;  // diagnostic: what sent the row to the two-sweep kernel
@@ -1784,14 +1949,14 @@ __global__ void __launch_bounds__(kStreamBlock) __attribute__((amdgpu_waves_per_
             if (largest)
                 for_each_tile<2>(
                     src, 0u, 1u, ntiles,
-                    [&](const typename Source::Tile& cur) { note(cur, stream_tile<true, true, Source, DT>(src, cur, thr)); },
-                    [&](const typename Source::Tile& cur) { note(cur, stream_tile<false, true, Source, DT>(src, cur, thr)); },
+                    [&](const typename Source::Tile& cur) __attribute__((always_inline)) { note(cur, stream_tile<true, true, Source, DT>(src, cur, thr)); },
+                    [&](const typename Source::Tile& cur) __attribute__((always_inline)) { note(cur, stream_tile<false, true, Source, DT>(src, cur, thr)); },
                     c0, c1);
             else
                 for_each_tile<2>(
                     src, 0u, 1u, ntiles,
-                    [&](const typename Source::Tile& cur) { note(cur, stream_tile<true, false, Source, DT>(src, cur, thr)); },
-                    [&](const typename Source::Tile& cur) { note(cur, stream_tile<false, false, Source, DT>(src, cur, thr)); },
+                    [&](const typename Source::Tile& cur) __attribute__((always_inline)) { note(cur, stream_tile<true, false, Source, DT>(src, cur, thr)); },
+                    [&](const typename Source::Tile& cur) __attribute__((always_inline)) { note(cur, stream_tile<false, false, Source, DT>(src, cur, thr)); },
                     c0, c1);
             if (c0 == 0) RTOPK_STAMP(6);
             // (each lane reads back only what it wrote itself: no barrier.)  A lane collects up to four hits and
@@ -2024,7 +2189,10 @@ static rtopk_status launch_all(const Params& P, const Config& c, bool scaled, hi
             hipLaunchKernelGGL((k_pass0_after_prefilter<DT, false>), grid, block, 0, st, P);
     }
     for (int p = 1; p <= c.multi_last && p < c.npass; ++p) {
-        hipLaunchKernelGGL((k_classify_cand<DT>), grid, block, 0, st, P, p);
+        if (nt)
+            hipLaunchKernelGGL((k_classify_cand<DT, true>), grid, block, 0, st, P, p);
+        else
+            hipLaunchKernelGGL((k_classify_cand<DT, false>), grid, block, 0, st, P, p);
     }
     hipLaunchKernelGGL((k_finish<DT>), dim3(batch), dim3(kRowBlock), 0, st, P);
     if (P.flags & RTOPK_FLAG_SORTED) launch_sort<DT>(P, st);

@@ -24,7 +24,7 @@ def _both(bits, dtype, k, largest, flags=0, seed=0):
             before = torch.cuda.memory_allocated()
             B.rtopk_select_static(x.data_ptr(), batch, n, k, dtype, largest, flags, seed, vals.data_ptr(),
                                   idx.data_ptr(), stream)
-            assert torch.cuda.memory_allocated() == before
+            assert torch.cuda.memory_allocated() <= before      # (torch may release, never acquire, meanwhile)
         else:
             need = B.rtopk_workspace_bytes(batch, n, k, dtype, flags)
             ws = torch.empty(need, dtype=torch.uint8, device="cuda")
