@@ -37,21 +37,38 @@ def bytes_moved(tr, n, es, k):
         return 0, "skipped"
     if ps[0].where == 4:                                   # one-sweep row kernel: X once (+ its first part again, cached)
         return es * n + out, "one sweep"
-    later = sum(8 * p.cand_before + 8 * p.cand_after for p in ps[1:] if p.source != 3)
+    def pass_bytes(i):
+        """read of pass i's source + write of its candidates (an in-place pass writes none; after in-place passes
+        that began over X the source is still X)"""
+        p = ps[i]
+        if p.source == 3:
+            return 0
+        src_in_x = i > 0 and (ps[i - 1].window >> 26) & 1
+        rd = es * n if src_in_x else 8 * p.cand_before
+        if i > 0 and (ps[i - 1].window >> 25) & 1 and not src_in_x:
+            q = i - 1                                      # the array the in-place chain reads is as long as when it was written
+            while q > 0 and (ps[q - 1].window >> 25) & 1 and not (ps[q - 1].window >> 26) & 1:
+                q -= 1
+            rd = 8 * ps[q].cand_before
+        wr = 0 if (p.window >> 25) & 1 else 8 * p.cand_after
+        return rd + wr
+
+    later = sum(pass_bytes(i) for i in range(1, len(ps)))
+    first_wr = 0 if (ps[0].window >> 25) & 1 else 8 * ps[0].cand_after
     if ps[0].where == 3:                                   # one workgroup per row
         if n * es <= 256 * 1024:
-            return es * n + 8 * ps[0].cand_after + later + out, "row in registers"
-        return 2 * es * n + 8 * ps[0].cand_after + later + out, "one workgroup, two sweeps"
+            return es * n + first_wr + later + out, "row in registers"
+        return 2 * es * n + first_wr + later + out, "one workgroup, two sweeps"
     if tr.pre_elems:                                       # sample + one sweep that counts and keeps
         b = es * tr.pre_elems + es * n + 8 * tr.pre_kept
         if tr.pre_missed:
-            b += es * n + 8 * ps[0].cand_after
+            b += es * n + first_wr
             return b + later + out, "sample + counting sweep + second sweep"
         if tr.pre_merged:                                  # pass 0 has no sweep; pass 1 reads all that was kept
-            rest = sum(8 * p.cand_before + 8 * p.cand_after for p in ps[2:] if p.source != 3)
+            rest = sum(pass_bytes(i) for i in range(2, len(ps)))
             return b + 8 * tr.pre_kept + 8 * ps[1].cand_after + rest + out, "sample + one sweep, two-digit pass"
-        return b + 8 * tr.pre_kept + 8 * ps[0].cand_after + later + out, "sample + one sweep"
-    return 2 * es * n + 8 * ps[0].cand_after + later + out, "two sweeps"
+        return b + 8 * tr.pre_kept + first_wr + later + out, "sample + one sweep"
+    return 2 * es * n + first_wr + later + out, "two sweeps"
 
 
 def main() -> int:

@@ -46,6 +46,10 @@ static rtopk_status make_config(int64_t batch, int64_t n, int64_t k, rtopk_dtype
     if (path == 0) {
         // short rows, or enough rows to occupy every compute unit: one workgroup per row
         path = (n <= (1 << 18) || (batch >= 256 && n <= (1 << 20))) ? 1 : 2;
+        // ... unless a large part of every row is wanted: a workgroup that owns a row goes through its phases one
+        // after the other (1024 rows of 2^17 bf16 keys, k = 8192: 51 + 36 us per row, 360 us in all), while the
+        // grid kernels, one workgroup per row here, keep several rows per compute unit in flight (277 us)
+        if (path == 1 && batch >= 256 && batch <= 65535 && n >= 65536 && k * 16 >= n) path = 2;
         if (batch > 65535) path = 1;
     }
     // The one-sweep kernel sets aside a few hundred elements of a row (its bound comes from the row's first
@@ -74,8 +78,14 @@ static rtopk_status make_config(int64_t batch, int64_t n, int64_t k, rtopk_dtype
     if (tn && (tn->prefilter < -1 || tn->prefilter > 1)) return RTOPK_ERR_INVALID_ARG;
     const int pre_knob = tn ? tn->prefilter : 0;
     const bool scaling_on = (flags & RTOPK_FLAG_SCALING) && dt == RTOPK_F32;
+    // (inputs of 64 to 256 MB: two sweeps from the caches cost little more than one, and the call is bound by its
+    // launches; for fp32 keys the prefilter still wins where pass 0 would otherwise write many candidates -- 2^24
+    // keys, k = 2^16: 62 against 82 us, k = 2^12: 61 against 65, k = 16: 61 against 58; 2^26 fp16 keys that all
+    // fall into one bin lost 100 us to the counting sweep that then stands before the two others)
+    const int64_t in_bytes = batch * n * eb;
     if (path == 2 && !scaling_on &&
-        (pre_knob == 1 || (pre_knob == 0 && batch * n * eb >= ((int64_t)256 << 20) && k <= n / 32))) {
+        (pre_knob == 1 || (pre_knob == 0 && k <= n / 32 &&
+                           (in_bytes >= ((int64_t)256 << 20) || (dt == RTOPK_F32 && in_bytes >= ((int64_t)64 << 20) && k * 4096 >= n))))) {
         c->prefilter = true;
         c->pre_stride = 31;
     }
@@ -87,7 +97,9 @@ static rtopk_status make_config(int64_t batch, int64_t n, int64_t k, rtopk_dtype
             // against 515)
             // (16-bit keys: whole bins of an 11-bit digit are kept, more of the row; 2^29 fp16 keys, k = 2^20:
             // 260 us with 512, 346 with 256; bf16 with k = 50 or 2^10: no difference)
-            int64_t want = (c->prefilter && dt == RTOPK_F32 && k <= n / 256 ? 256 : 512) / batch;
+            // (and one for inputs that the caches hold: 2^24 fp32 keys, two sweeps: 53-61 us against 58-65)
+            const bool cached = in_bytes <= ((int64_t)128 << 20);
+            int64_t want = ((c->prefilter && dt == RTOPK_F32 && k <= n / 256) || cached ? 256 : 512) / batch;
             if (want < 1) want = 1;
             G = (int)want;
         }
