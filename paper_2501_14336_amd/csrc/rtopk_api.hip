@@ -97,8 +97,9 @@ static rtopk_status make_config(int64_t batch, int64_t n, int64_t k, rtopk_dtype
             // against 515)
             // (16-bit keys: whole bins of an 11-bit digit are kept, more of the row; 2^29 fp16 keys, k = 2^20:
             // 260 us with 512, 346 with 256; bf16 with k = 50 or 2^10: no difference)
-            // (and one for inputs that the caches hold: 2^24 fp32 keys, two sweeps: 53-61 us against 58-65)
-            const bool cached = in_bytes <= ((int64_t)128 << 20);
+            // (and one for inputs that the caches hold: 2^24 fp32 keys, two sweeps: 53-61 us against 58-65; not
+            // 128 MB: 2^26 fp16 keys of few distinct values, 355-385 us against 270-303)
+            const bool cached = in_bytes <= ((int64_t)64 << 20);
             int64_t want = ((c->prefilter && dt == RTOPK_F32 && k <= n / 256) || cached ? 256 : 512) / batch;
             if (want < 1) want = 1;
             G = (int)want;

@@ -1803,6 +1803,7 @@ constexpr u32 kStreamList = 2048;                    // elements set aside per r
 constexpr u32 kStreamRank = 2 * kStreamBlock - 64;   // candidates ranked directly, at most (two per lane)
 constexpr u32 kStreamWide = kMaxBins + 8;            // words for the copies of the histogram (1 x 4097, 2 x 2049)
 constexpr u32 kStreamChunk = 16;                     // tiles swept between two rounds of fetching the hits
+constexpr unsigned long long kStreamStagger = 1000;  // ticks of the 100 MHz wall clock between the starts of two groups
 
 struct SharedStream {
     union {
@@ -1875,6 +1876,15 @@ __global__ void __launch_bounds__(kStreamBlock) __attribute__((amdgpu_waves_per_
     const int row = blockIdx.x;
     rtopk_row_trace* st = row_state(P, row);
     const u32 tid = threadIdx.x, lane = lane_id();
+    // Four of these workgroups share a compute unit, and workgroups launched together march through their phases
+    // together: all count (LDS), then all sweep (memory), then all fetch (latency).  The groups of 256 workgroups --
+    // one per compute unit each -- therefore start 10 us apart, for as many groups as are resident at once, so that
+    // on a compute unit one row's trip to memory overlaps the others' counting (1024 rows of 2^17 bf16 keys:
+    // 82 -> 75 us; 3 or 6 us apart: 80; 15 us: 84).  The wait is bounded by the clock it reads.
+    {
+        const unsigned long long t0 = wall_clock64(), wait = (unsigned long long)((blockIdx.x >> 8) & 3u) * kStreamStagger;
+        while (wall_clock64() - t0 < wait) __builtin_amdgcn_s_sleep(16);
+    }
     RTOPK_STAMP(0);
     const RowShape rs = row_shape<KeyOf<DT>::kBytes>(P, row);
     init_row<DT>(P, row, st, rs);
