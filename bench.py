@@ -273,8 +273,11 @@ def main() -> int:
         rows = []
         want = args.only_config
 
-        def wanted(name):
+        def wanted(name):                       # a block ("C3") runs if the prefix lies inside it or it inside the prefix;
             return name.startswith(want) or want.startswith(name)
+
+        def row_wanted(name):                   # a row of a block only if its own name starts with the prefix
+            return name.startswith(want) or (want.startswith(name) and " " not in name)
 
         def ms_of(name):
             for r in rows:
@@ -312,27 +315,36 @@ def main() -> int:
             w2 = None
             for kk in (16, 256, 4096, 65536, 1 << 20):
                 for largest in (True, False):
+                    if not row_wanted("C2 k=%d %s" % (kk, "largest" if largest else "smallest")):
+                        continue
                     e, w2 = row("C2 k=%d %s" % (kk, "largest" if largest else "smallest"), x2, b2, kk, largest, False,
                                 B.RTOPK_F32, 1, 1 << 24, 4, wsb=w2)
                     rows.append(e)
-            med, best, _, w2, _, _ = time_rows(x2, 4096, True, False, B.RTOPK_F32, 1, 1 << 24, sorted_out=True, wsb=w2)
-            rows.append({"config": "C2 sorted k=4096", "ms": med, "sort_share_of_call": 1.0 - ms_of("C2 k=4096 largest") / med,
-                         "note": "bitonic sort of the k pairs in LDS after the selection (the paper counts 0.1-0.6 % "
-                                 "for its sort, Section 5.2)"})
+            if row_wanted("C2 sorted k=4096") and ms_of("C2 k=4096 largest") is not None:
+                med, best, _, w2, _, _ = time_rows(x2, 4096, True, False, B.RTOPK_F32, 1, 1 << 24, sorted_out=True, wsb=w2)
+                rows.append({"config": "C2 sorted k=4096", "ms": med,
+                             "sort_share_of_call": 1.0 - ms_of("C2 k=4096 largest") / med,
+                             "note": "bitonic sort of the k pairs in LDS after the selection (the paper counts 0.1-0.6 % "
+                                     "for its sort, Section 5.2)"})
             del x2, w2
         if wanted("C3"):
             b3 = W.config3()
             x3 = torch.from_numpy(b3.view(np.int16)).to(dev).view(torch.bfloat16)
             w3 = None
             for kk in (50, 1024, 8192):
+                if not row_wanted("C3 k=%d" % kk):
+                    continue
                 e, w3 = row("C3 k=%d" % kk, x3, b3, kk, True, False, B.RTOPK_BF16, 1024, 131072, 2,
                             check_rows=tuple(range(0, 1024, 97)), wsb=w3)
                 rows.append(e)
             for kk in (50, 8192):
+                if not row_wanted("C3 sorted k=%d" % kk) or ms_of("C3 k=%d" % kk) is None:
+                    continue
                 med, best, _, w3, _, _ = time_rows(x3, kk, True, False, B.RTOPK_BF16, 1024, 131072, sorted_out=True, wsb=w3)
                 rows.append({"config": "C3 sorted k=%d" % kk, "ms": med, "sort_share_of_call": 1.0 - ms_of("C3 k=%d" % kk) / med})
-            out["batch_case"] = {"workload": "config3: 1024 x 131072 bf16 logits N(0,9)+8 spikes, k=50, largest",
-                                 "keys_per_s": 1024 * 131072 / (ms_of("C3 k=50") * 1e-3), "ms_per_step": ms_of("C3 k=50")}
+            if ms_of("C3 k=50") is not None:
+                out["batch_case"] = {"workload": "config3: 1024 x 131072 bf16 logits N(0,9)+8 spikes, k=50, largest",
+                                     "keys_per_s": 1024 * 131072 / (ms_of("C3 k=50") * 1e-3), "ms_per_step": ms_of("C3 k=50")}
             del x3, w3
         torch.cuda.empty_cache()
         if wanted("C5"):
@@ -346,6 +358,9 @@ def main() -> int:
                     w5 = None
                     for largest in ((True, False) if case != "a" else (True,)):
                         for scaling in ((False, True) if code == B.RTOPK_F32 else (False,)):
+                            if not row_wanted("C5%s %s %s%s" % (case, ("f32", "f16")[code], "largest" if largest else "smallest",
+                                                                " scaled" if scaling else "")):
+                                continue
                             e, w5 = row("C5%s %s %s%s" % (case, ("f32", "f16")[code], "largest" if largest else "smallest",
                                                           " scaled" if scaling else ""), xd, bits, 1 << 16, largest, scaling,
                                         code, 1, 1 << 26, esz, wsb=w5)
