@@ -1397,7 +1397,9 @@ __device__ __forceinline__ float init_row(const Params& P, int row, rtopk_row_tr
 template <int DT>
 __global__ void __launch_bounds__(256) k_init(Params P) {
     const int row = blockIdx.x;
-    for (int h = 0; h < kHostHistBuffers; ++h) {
+    // (the sample's histogram and the second digit's exist only with the prefilter sweep)
+    const int buffers = P.pre_stride != 0 ? kHostHistBuffers : kHistRing;
+    for (int h = 0; h < buffers; ++h) {
         u32* ghist = P.ghist + ((size_t)h * P.batch + row) * kMaxBins;
         for (int j = threadIdx.x; j < kMaxBins; j += 256) ghist[j] = 0;
     }

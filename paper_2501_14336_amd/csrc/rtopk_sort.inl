@@ -106,7 +106,7 @@ __global__ void __launch_bounds__(kSortBlock) k_sort_pack(Params P) {
     if (blockIdx.x == 0 && threadIdx.x < sizeof(SortState) / 4) ((u32*)sort_state(P, row))[threadIdx.x] = 0;
 }
 
-// histogram of pass j's digit over each workgroup's chunk: table[bin][workgroup]
+// histogram of pass j's digit over each workgroup's chunk: table[workgroup][bin]
 template <int DT>
 __global__ void __launch_bounds__(kSortBlock) k_sort_hist(Params P, int j) {
     __shared__ u32 h[kSortBins];
@@ -120,42 +120,45 @@ __global__ void __launch_bounds__(kSortBlock) k_sort_hist(Params P, int j) {
     for (u32 i = begin + threadIdx.x; i < end; i += kSortBlock) atomicAdd(&h[(u32)(src[i] >> (8 * j)) & 255u], 1u);
     __syncthreads();
     u32* table = P.sort_hist + (size_t)row * kSortBins * P.Gs;
-    if (threadIdx.x < kSortBins) table[(size_t)threadIdx.x * P.Gs + blockIdx.x] = h[threadIdx.x];
+    if (threadIdx.x < kSortBins) table[(size_t)blockIdx.x * kSortBins + threadIdx.x] = h[threadIdx.x];
 }
 
-// exclusive scan of the table in (bin, workgroup) order: where each workgroup's elements of each bin go
+// exclusive scan of the table in (bin, workgroup) order: where each workgroup's elements of each bin go.
+// Four threads share a bin, each owning a quarter of the workgroups' counts of that bin; the 256 threads of a
+// quarter read consecutive words (the table is laid out [workgroup][bin]).  One scan over the threads' sums,
+// taken in (bin, quarter) order, gives every thread the offset its stretch starts at.
 template <int DT>
 __global__ void __launch_bounds__(kRowBlock) k_sort_scan(Params P, int j) {
+    static_assert(kRowBlock == 4 * kSortBins, "four threads per bin");
     __shared__ u32 wsum[kRowBlock / 64];
-    __shared__ u32 carry, all_in_one;
+    __shared__ u32 sums[kRowBlock], upto[kRowBlock];
+    __shared__ u32 all_in_one;
     const int row = blockIdx.x;
     const u32 tid = threadIdx.x;
     const u32 row_k = row_shape<KeyOf<DT>::kBytes>(P, row).k;
     u32* table = P.sort_hist + (size_t)row * kSortBins * P.Gs;
-    const u32 total = (u32)kSortBins * (u32)P.Gs;
-    if (tid == 0) {
-        carry = 0;
-        all_in_one = 0;
-    }
+    const u32 Gs = (u32)P.Gs, per = (Gs + 3u) / 4u;
+    const u32 bin = tid & (u32)(kSortBins - 1), quarter = tid / (u32)kSortBins;
+    const u32 w0 = quarter * per < Gs ? quarter * per : Gs, w1 = w0 + per < Gs ? w0 + per : Gs;
+    if (tid == 0) all_in_one = 0;
+    u32 sum = 0;
+    for (u32 w = w0; w < w1; ++w) sum += table[(size_t)w * kSortBins + bin];
+    sums[bin * 4u + quarter] = sum;
     __syncthreads();
-    // is the digit the same for every key?  (then some bin's row of the table sums to k)
-    if (tid < kSortBins) {
-        u32 s = 0;
-        for (int w = 0; w < P.Gs; ++w) s += table[(size_t)tid * P.Gs + w];
-        if (s == row_k) all_in_one = 1;  // (also a row with nothing to sort: every count is 0)
-    }
+    const u32 v = sums[tid];  // thread order is now (bin, quarter) order
+    const u32 incl = block_inclusive_scan<kRowBlock>(v, wsum);
+    upto[tid] = incl;
+    __syncthreads();
+    // is the digit the same for every key?  (then some bin holds all k; also a row with nothing to sort)
+    if ((tid & 3u) == 3u && incl - (tid >= 4u ? upto[tid - 4u] : 0u) == row_k) all_in_one = 1;
     __syncthreads();
     const bool skip = all_in_one != 0;
     if (!skip) {
-        for (u32 base = 0; base < total; base += kRowBlock) {
-            const u32 i = base + tid;
-            const u32 v = i < total ? table[i] : 0u;
-            const u32 incl = block_inclusive_scan<kRowBlock>(v, wsum);
-            const u32 c = carry;
-            if (i < total) table[i] = c + incl - v;
-            __syncthreads();
-            if (tid == kRowBlock - 1) carry = c + incl;
-            __syncthreads();
+        u32 run = upto[bin * 4u + quarter] - sum;
+        for (u32 w = w0; w < w1; ++w) {
+            const u32 c = table[(size_t)w * kSortBins + bin];
+            table[(size_t)w * kSortBins + bin] = run;
+            run += c;
         }
     }
     if (tid == 0) {
@@ -179,7 +182,7 @@ __global__ void __launch_bounds__(kSortBlock) k_sort_scatter(Params P, int j) {
     const u64* src = sort_buffer(P, st->cur[j], row);
     u64* dst = sort_buffer(P, 1u - st->cur[j], row);
     const u32* table = P.sort_hist + (size_t)row * kSortBins * P.Gs;
-    if (tid < kSortBins) base[tid] = table[(size_t)tid * P.Gs + blockIdx.x];
+    if (tid < kSortBins) base[tid] = table[(size_t)blockIdx.x * kSortBins + tid];
     u32 begin, end;
     sort_chunk(P, row_k, blockIdx.x, begin, end);
     for (u32 t0 = begin; t0 < end; t0 += kSortBlock) {
