@@ -217,10 +217,13 @@ typedef struct {
     float a_s;                 /* the element subtracted under RTOPK_FLAG_SCALING (0 if unused)      */
     uint32_t error;            /* 0, or a bit set if the device saw an impossible state              */
     uint32_t redo;             /* 1: the one-sweep row kernel left this row to the two-sweep kernel
-                                  (which clears the whole record when it takes the row over)         */
-    uint32_t redo_why;         /* diagnostic, with redo: 1 inf/NaN in the first part, 2 first part
-                                  shorter than k, 3 bin edge not a number, 5 list full, 6 too many
-                                  candidates in the chosen bin, 7 list expected to overflow           */
+                                  (which clears the record, redo_why excepted, when it takes the row
+                                  over)                                                              */
+    uint32_t redo_why;         /* diagnostic; non-zero: the one-sweep kernel handed the row over.
+                                  1 inf/NaN in the part counted first, 2 that part shorter than k,
+                                  3 bin edge not a number, 5 list full, 6 too many candidates in the
+                                  chosen bin, 7 list expected to overflow, 8 the sample misled (fewer
+                                  than k elements at or above its bound)                              */
     uint32_t pre_elems;        /* elements in the row's sample, counted before a prefilter sweep
                                   (0: no prefilter, the whole row was counted)                       */
     uint32_t pre_bound;        /* with a prefilter: the bin taken from the sample; the sweep kept the

@@ -48,8 +48,9 @@ static rtopk_status make_config(int64_t batch, int64_t n, int64_t k, rtopk_dtype
         path = (n <= (1 << 18) || (batch >= 256 && n <= (1 << 20))) ? 1 : 2;
         // ... unless a large part of every row is wanted: a workgroup that owns a row goes through its phases one
         // after the other (1024 rows of 2^17 bf16 keys, k = 8192: 51 + 36 us per row, 360 us in all), while the
-        // grid kernels, one workgroup per row here, keep several rows per compute unit in flight (277 us)
-        if (path == 1 && batch >= 256 && batch <= 65535 && n >= 65536 && k * 16 >= n) path = 2;
+        // grid kernels, one workgroup per row here, keep several rows per compute unit in flight (277 us; k = 2048:
+        // 281 against 230, k = 1024: 217 against 224)
+        if (path == 1 && batch >= 256 && batch <= 65535 && n >= 65536 && k * 64 >= n) path = 2;
         if (batch > 65535) path = 1;
     }
     // The one-sweep kernel sets aside a few hundred elements of a row (its bound comes from the row's first
@@ -58,7 +59,11 @@ static rtopk_status make_config(int64_t batch, int64_t n, int64_t k, rtopk_dtype
     // kernel, so the choice never changes the result.
     bool one_sweep = path == 3;
     if (path == 3) path = 1;
-    else if (path == 1 && (!tn || tn->path == 0) && k <= 256 && n >= 16384 && (batch >= 16 || n >= 131072)) one_sweep = true;
+    // (k up to 512 on rows of 64K keys up: the bound then comes from a sample of the row and is checked afterwards --
+    // 1024 rows of 2^17 bf16 keys, k = 1024: see the measurements beside the kernel)
+    else if (path == 1 && (!tn || tn->path == 0) && (k <= 256 || (k <= 512 && n >= 65536)) && n >= 16384 &&
+             (batch >= 16 || n >= 131072))
+        one_sweep = true;
     if (path == 2 && batch > 65535) return RTOPK_ERR_INVALID_ARG;  // rows are the grid's y dimension
     // 16-bit keys on long rows: a 12-bit first digit (4 bits left for the second) instead of 11 + 5 -- the first
     // sweep then keeps a bin of half the width (bf16 logits, 64 x 2^22, k = 50: 200 -> 167 us; 2^29 uniform bf16

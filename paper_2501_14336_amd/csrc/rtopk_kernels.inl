@@ -416,7 +416,10 @@ __device__ __forceinline__ Selection hist_phase(const Source& src, const Params&
     HistSlot hs{sm.hist};
     u32 copies = 1;
     const u32 stride = (u32)nb + 1u;
-    if (SINGLE) {
+    // (with many workgroups per row one copy: two copies changed nothing on 2^28 uniform fp32 keys, 365 against
+    // 366 us, nor on 1024 rows of 2^17 bf16 logits with one workgroup per row, 222 against 219-224 us)
+    constexpr bool kSpread = SINGLE;
+    if (kSpread) {
         constexpr u32 kWideLog2 = B == 1024 ? 14 : 13;
         static_assert(sizeof(sm.wide) / 4 >= (1u << kWideLog2) + 8, "wide histogram size");
         const u32 room = kWideLog2 - ctx.pi.bits;
@@ -424,7 +427,7 @@ __device__ __forceinline__ Selection hist_phase(const Source& src, const Params&
         hs.h = sm.wide + (lane & (copies - 1u)) * stride;
     }
     auto clear = [&]() __attribute__((always_inline)) {
-        if (SINGLE) {
+        if (kSpread) {
             for (u32 j = tid; j < copies * stride; j += B) sm.wide[j] = 0;
         } else {
             for (int j = tid; j < nb; j += B) sm.hist[j] = 0;
@@ -534,6 +537,10 @@ __device__ __forceinline__ Selection hist_phase(const Source& src, const Params&
     if (SINGLE) {
         return select_pass<B>([&](u32 j, bool*) __attribute__((always_inline)) { return copies_of(j); }, nb, e, sm, st);
     } else {
+        if (kSpread) {
+            for (int j = tid; j < nb; j += B) sm.hist[j] = copies_of((u32)j);
+            __syncthreads();
+        }
         // (the sample's histogram has a buffer of its own; nobody needs its per-workgroup records)
         u32* ghist = P.pre_stride != 0 ? hist_buffer(P, kHistSample, row) : global_hist(P, p, row);
         for (int j = tid; j < nb; j += B) {
@@ -1376,11 +1383,14 @@ __device__ __forceinline__ u64 mix64(u64 z) {
 }
 
 // Called by every thread of a workgroup of at least 128 threads; returns a_s to thread 0 only.
+// keep_why: the row was handed over by the one-sweep kernel; what it noted as the reason stays in the record.
 template <int DT>
-__device__ __forceinline__ float init_row(const Params& P, int row, rtopk_row_trace* st, const RowShape& rs) {
+__device__ __forceinline__ float init_row(const Params& P, int row, rtopk_row_trace* st, const RowShape& rs,
+                                          bool keep_why = false) {
     static_assert(sizeof(rtopk_row_trace) / 4 <= 128 && offsetof(rtopk_row_trace, a_s) == 0, "trace layout");
+    static_assert(offsetof(rtopk_row_trace, redo_why) == 12, "trace layout");
     u32* w = (u32*)st;
-    if (threadIdx.x >= 2 && threadIdx.x < sizeof(rtopk_row_trace) / 4) w[threadIdx.x] = 0;
+    if (threadIdx.x >= 2 && threadIdx.x < sizeof(rtopk_row_trace) / 4 && !(keep_why && threadIdx.x == 3)) w[threadIdx.x] = 0;
     float a_s = 0.0f;
     if (threadIdx.x == 0) {
         if (DT == RTOPK_F32 && (P.flags & RTOPK_FLAG_SCALING) && rs.n != 0) {
@@ -1686,7 +1696,7 @@ __global__ void __launch_bounds__(kRowBlock) k_row(Params P, bool only_redo) {
     rtopk_row_trace* st = row_state(P, row);
     if (only_redo && st->redo != 1u) return;
     const RowShape rs = row_shape<KeyOf<DT>::kBytes>(P, row);
-    const float drawn = init_row<DT>(P, row, st, rs);
+    const float drawn = init_row<DT>(P, row, st, rs, only_redo);
     if (rs.k == 0) return;  // (ragged batches: an empty row, or nothing wanted from it)
     if (threadIdx.x == 0) sm.a_s = drawn;
     __syncthreads();
@@ -1747,7 +1757,7 @@ __global__ void __launch_bounds__(kRowBlock) k_row_resident(Params P, bool only_
     unsigned long long tt[6];
     tt[4] = wall_clock64();
 #endif
-    const float drawn = init_row<DT>(P, row, st, rs);
+    const float drawn = init_row<DT>(P, row, st, rs, only_redo);
     if (rs.k == 0) return;  // (ragged batches: an empty row, or nothing wanted from it)
     if (threadIdx.x == 0) sm.a_s = drawn;
     __syncthreads();
@@ -1801,12 +1811,16 @@ __global__ void __launch_bounds__(kRowBlock) k_row_resident(Params P, bool only_
 // rows.
 // ------------------------------------------------------------------------------------------------
 constexpr int kStreamBlock = 512;
-constexpr u32 kStreamList = 2048;                    // elements set aside per row, at most
+constexpr u32 kStreamList = 2048;                    // elements set aside per row, at most (k <= kStreamSmallK)
+constexpr u32 kStreamListMid = 2816;                 // ... for larger k: what still lets four workgroups share 160 KB of LDS
+constexpr u32 kStreamSmallK = 256;                   // up to here the bound comes from the row's first part, beyond from a sample
+constexpr u32 kStreamSampleStride = 4;               // the sample: every 4th tile of the row
 constexpr u32 kStreamRank = 2 * kStreamBlock - 64;   // candidates ranked directly, at most (two per lane)
 constexpr u32 kStreamWide = kMaxBins + 8;            // words for the copies of the histogram (1 x 4097, 2 x 2049)
 constexpr u32 kStreamChunk = 16;                     // tiles swept between two rounds of fetching the hits
 constexpr unsigned long long kStreamStagger = 1000;  // ticks of the 100 MHz wall clock between the starts of two groups
 
+template <u32 LIST>
 struct SharedStream {
     union {
         u32 wide[kStreamWide];              // copies of the first part's histogram (see HistSlot); then the lanes'
@@ -1817,7 +1831,7 @@ struct SharedStream {
             u64 rank_ext[2 * kStreamBlock];
         };
     };
-    uint2 list[kStreamList];                // (raw bits, index) of the elements set aside
+    uint2 list[LIST];                       // (raw bits, index) of the elements set aside
     u32 wsum[kStreamBlock / 64];
     u32 selv[5];
     u32 nlist, runW, runC;
@@ -1869,9 +1883,10 @@ __device__ __forceinline__ u32 stream_tile(const Source& src, const typename Sou
     return bits;
 }
 
-template <int DT>
+template <int DT, u32 LIST>
 __global__ void __launch_bounds__(kStreamBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) k_row_stream(Params P) {
-    __shared__ SharedStream sm;
+    static_assert(4 * sizeof(SharedStream<LIST>) <= 160 * 1024, "four workgroups per compute unit");
+    __shared__ SharedStream<LIST> sm;
     constexpr int B = kStreamBlock;
     constexpr bool SINGLE = true;  // (for the diagnostic stamps)
     typedef KeySource<DT, B, key_vecs<DT>(), false> Source;
@@ -1910,16 +1925,21 @@ __global__ void __launch_bounds__(kStreamBlock) __attribute__((amdgpu_waves_per_
 
     // ---- countBin on the first part of the row: an eighth of it, more for larger k (about k * row / part
     // elements will be set aside: keep that near 512), and enough to hold k elements
+    // For larger k a first part long enough would be most of the row.  There the bound comes from a SAMPLE -- every
+    // 4th tile, so a trend along the row cannot mislead it -- for a rank with a margin (as the grid prefilter's), and
+    // is checked afterwards: if the list ends up with at least k elements, the k-th key is in it and the list is the
+    // top of the row, exactly as with a guaranteed bound; if not, the sample misled and the row is handed over.
     constexpr u32 kTileElems = (u32)B * Source::kSlots;
+    const bool sampled = rs.k > kStreamSmallK;
     u32 t0 = (ntiles + 7u) / 8u;
     const u32 by_k = (u32)(((u64)rs.k * ntiles + 511u) / 512u);
     const u32 need = (rs.k + src.lead + kTileElems - 1u) / kTileElems;
     if (t0 < by_k) t0 = by_k;
     if (t0 < need) t0 = need;
-    if (t0 > ntiles) t0 = ntiles;
+    if (t0 > ntiles || sampled) t0 = ntiles;
     auto nothing = []() __attribute__((always_inline)) {};
     for_each_tile<2>(
-        src, 0u, 1u, ntiles,
+        src, 0u, sampled ? kStreamSampleStride : 1u, ntiles,
         [&](const typename Source::Tile& cur) __attribute__((always_inline)) { hist_tile_raw<true, Source>(src, cur, ctx, hs); },
         [&](const typename Source::Tile& cur) __attribute__((always_inline)) { hist_tile_raw<false, Source>(src, cur, ctx, hs); }, 0u, t0);
     __syncthreads();
@@ -1928,24 +1948,38 @@ __global__ void __launch_bounds__(kStreamBlock) __attribute__((amdgpu_waves_per_
     float thr = 0.0f;
     u32 b0 = 0;
     {
-        // how many elements have been counted?  (tiles [0, t0) hold elements [0, t0 * tile - lead) of the row)
-        const u64 seen64 = (u64)t0 * kTileElems - src.lead;
-        const u32 seen = seen64 < (u64)rs.n ? (u32)seen64 : rs.n;
+        // how many elements have been counted?  (tiles [0, t0) hold elements [0, t0 * tile - lead) of the row; of the
+        // sampled tiles 0, 4, 8, ... only the row's last one can be short)
+        u32 seen, want = rs.k;
+        if (sampled) {
+            const u32 ns = (ntiles + kStreamSampleStride - 1u) / kStreamSampleStride;
+            u64 s64 = (u64)ns * kTileElems - src.lead;
+            if ((ntiles - 1u) % kStreamSampleStride == 0u) s64 -= (u64)ntiles * kTileElems - src.lead - rs.n;
+            seen = (u32)s64;
+            // the sample rank that stands for the row's k-th key: its share, an eighth more, eight standard deviations
+            // of a binomial count, and 16
+            const u32 ks = (u32)(((u64)rs.k * seen + rs.n - 1u) / rs.n);
+            want = ks + ks / 8u + 8u * (u32)__builtin_sqrtf((float)ks) + 16u;
+        } else {
+            const u64 seen64 = (u64)t0 * kTileElems - src.lead;
+            seen = seen64 < (u64)rs.n ? (u32)seen64 : rs.n;
+        }
         bool distrust = false;
         Selection s0{};
-        if (seen >= rs.k) s0 = select_from_counts<B>(counts, nb, rs.k, sm, st, nothing, &distrust);
+        if (seen >= want) s0 = select_from_counts<B>(counts, nb, want, sm, st, nothing, &distrust);
         b0 = s0.bin;
         // the bound as a number: set aside what is not below the lower edge of bin b0 ("largest"), or what
         // is below its upper edge ("smallest": keys are complemented, bin b0 is raw bin maxd - b0)
         const u32 maxd = (u32)nb - 1u;
         const u64 Bo = largest ? b0 : maxd - b0;
         const u64 T = (largest ? Bo : Bo + 1u) << ctx.pi.shift;
-        if (seen < rs.k) why = 2u;
+        if (seen < want) why = 2u;
         else if (distrust) why = 1u;
         else if (!threshold_number<DT>(T, &thr)) why = 3u;
         // the part's own share of bins >= b0, scaled to the row, is what the sweep will set aside: give up now
         // if that will not fit (a wide bin at the edge, say uniform data just below a power of two)
-        else if ((u64)(s0.above + s0.inside) * ntiles > (u64)(kStreamList * 3u / 4u) * t0) why = 7u;
+        else if (!sampled && (u64)(s0.above + s0.inside) * ntiles > (u64)(LIST * 3u / 4u) * t0) why = 7u;
+        else if (sampled && (u64)(s0.above + s0.inside) * rs.n > (u64)(LIST * 9u / 10u) * seen) why = 7u;
     }
     RTOPK_STAMP(2);
     if (why == 0) {
@@ -1982,10 +2016,10 @@ __global__ void __launch_bounds__(kStreamBlock) __attribute__((amdgpu_waves_per_
                 const u32 r0 = nh > 0 ? element(h0) : 0u, r1 = nh > 1 ? element(h1) : 0u;
                 const u32 r2 = nh > 2 ? element(h2) : 0u, r3 = nh > 3 ? element(h3) : 0u;
                 const u32 base = nh ? atomicAdd(&sm.nlist, nh) : 0u;
-                if (nh > 0 && base + 0 < kStreamList) sm.list[base + 0] = make_uint2(r0, h0);
-                if (nh > 1 && base + 1 < kStreamList) sm.list[base + 1] = make_uint2(r1, h1);
-                if (nh > 2 && base + 2 < kStreamList) sm.list[base + 2] = make_uint2(r2, h2);
-                if (nh > 3 && base + 3 < kStreamList) sm.list[base + 3] = make_uint2(r3, h3);
+                if (nh > 0 && base + 0 < LIST) sm.list[base + 0] = make_uint2(r0, h0);
+                if (nh > 1 && base + 1 < LIST) sm.list[base + 1] = make_uint2(r1, h1);
+                if (nh > 2 && base + 2 < LIST) sm.list[base + 2] = make_uint2(r2, h2);
+                if (nh > 3 && base + 3 < LIST) sm.list[base + 3] = make_uint2(r3, h3);
                 nh = 0;
             };
             for (u32 tl = 0; tl < c1 - c0; ++tl) {
@@ -2008,7 +2042,8 @@ __global__ void __launch_bounds__(kStreamBlock) __attribute__((amdgpu_waves_per_
             fetch();
         }
         __syncthreads();
-        if (sm.nlist > kStreamList) why = 5u;
+        if (sm.nlist > LIST) why = 5u;
+        else if (sampled && sm.nlist < rs.k) why = 8u;  // the sample misled: the k-th key lies below the bound
     }
     RTOPK_STAMP(3);
     Selection sel{};
@@ -2139,7 +2174,10 @@ static rtopk_status launch_all(const Params& P, const Config& c, bool scaled, hi
         const bool resident = P.n + (aligned ? 0 : kE - 1) <= cap;
         // small k, unscaled: the one-sweep kernel first; the two-sweep kernel then takes the rows it marked
         const bool one_sweep = c.one_sweep && !scaled;
-        if (one_sweep) hipLaunchKernelGGL((k_row_stream<DT>), dim3(batch), dim3(kStreamBlock), 0, st, P);
+        if (one_sweep && (u32)P.k <= kStreamSmallK)
+            hipLaunchKernelGGL((k_row_stream<DT, kStreamList>), dim3(batch), dim3(kStreamBlock), 0, st, P);
+        else if (one_sweep)
+            hipLaunchKernelGGL((k_row_stream<DT, kStreamListMid>), dim3(batch), dim3(kStreamBlock), 0, st, P);
         if (resident && scaled)
             hipLaunchKernelGGL((k_row_resident<DT, kScaledSrc>), dim3(batch), dim3(kRowBlock), 0, st, P, false);
         else if (resident)

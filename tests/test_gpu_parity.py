@@ -230,6 +230,42 @@ def test_one_sweep_kernel_and_its_hand_over():
     _run_and_check("k = n", W.normal(9000, 50).view(np.uint32), F32, 9000, True, tuning=T)
 
 
+def test_one_sweep_kernel_with_a_sampled_bound():
+    # 256 < k <= 512 on rows of 64K keys up: the one-sweep kernel takes its bound from every 4th tile of the row and
+    # checks afterwards that the list holds k elements (a guaranteed bound would need most of the row counted first)
+    T = dict(path=3)
+    short = lambda tr: all(r.where == 4 for r in tr.passes)
+    x = W.normal(5 * 70001, 141, sigma=3.0)      # odd length: every row starts off the 16-byte grid
+    for dtype, bits in ((F32, x.view(np.uint32)), (BF16, W.to_bf16_bits(x)), (F16, x.astype(np.float16).view(np.uint16))):
+        for k in (257, 400, 512):
+            for largest in (True, False):
+                trs = _run_and_check("sampled bound", bits.reshape(5, 70001), dtype, k, largest, tuning=T)
+                if dtype == F32:
+                    assert all(short(t) and t.redo_why == 0 for t in trs)
+    # the automatic choice takes this way for such batches (a few rows of the benchmark's shape)
+    trs = _run_and_check("sampled bound logits", W.llm_logits(20, 131072, 142), BF16, 300, True)
+    assert sum(short(t) for t in trs) >= 16
+    # a sample that misleads: the 250 largest elements all sit in sampled tiles (tile 0, 4, 8, ... of 8192 elements),
+    # so the bound taken from the sample lies above the k-th key and the list comes out short: reason 8, handed over
+    n = 16 * 8192
+    y = W.uniform01(n, 143)
+    pos = np.flatnonzero((np.arange(n) // 8192) % 4 == 0)[:: len(np.flatnonzero((np.arange(n) // 8192) % 4 == 0)) // 250][:250]
+    y[pos] = 100.0 + np.arange(len(pos), dtype=np.float32)
+    tr = _run_and_check("sample misled", y.view(np.uint32), F32, 400, True, tuning=T)[0]
+    assert not short(tr) and tr.redo_why == 8
+    # a row whose last tile is one of the sampled ones and is short; a trend along the row; specials in the sample
+    z = np.sort(W.normal(8 * 8192 + 100, 144))
+    for arr in (z, z[::-1].copy()):
+        for largest in (True, False):
+            _run_and_check("sampled sorted", arr.view(np.uint32), F32, 300, largest, tuning=T)
+    w = W.normal(90000, 145)
+    w[3], w[40000] = np.nan, np.inf
+    for largest in (True, False):
+        _run_and_check("sampled specials", w.view(np.uint32), F32, 300, largest, tuning=T)
+    # k above what the automatic choice sends this way (the kernel tries, or hands the row over)
+    _run_and_check("k beyond", W.normal(70000, 146).view(np.uint32), F32, 600, True, tuning=T)
+
+
 @pytest.mark.parametrize("G", [0, 3, 7])
 def test_prefilter_sweep(G):
     # many workgroups per row with the prefilter forced on: histogram of a sample of the row, one sweep that counts
