@@ -77,7 +77,9 @@ static rtopk_status make_config(int64_t batch, int64_t n, int64_t k, rtopk_dtype
     // probably lies at or below the k-th key's, and sweep X ONCE, counting every element's digit and keeping the
     // elements from that bin upwards; pass 0 then runs on what was kept.  If the full counts show the bin was
     // too high, pass 0 is the ordinary second sweep over X instead.
-    // It pays while k is well below n (what is kept is written out and read again).
+    // It pays while k is well below n (what is kept is written out and read again): 2^28 uniform fp32 keys,
+    // k = 2^24 (a sixteenth: 9 % of the row kept) 395 us against 526 with two sweeps; from k = 2^25 on the sample
+    // shows more than an eighth of the row in the bins to keep and the sweep would decline anyway.
     c->prefilter = false;
     c->pre_stride = 0;
     if (tn && (tn->prefilter < -1 || tn->prefilter > 1)) return RTOPK_ERR_INVALID_ARG;
@@ -88,24 +90,27 @@ static rtopk_status make_config(int64_t batch, int64_t n, int64_t k, rtopk_dtype
     // keys, k = 2^16: 62 against 82 us, k = 2^12: 61 against 65, k = 16: 61 against 58; 2^26 fp16 keys that all
     // fall into one bin lost 100 us to the counting sweep that then stands before the two others)
     const int64_t in_bytes = batch * n * eb;
+    // (up to a sixteenth of the row for fp32 inputs of 256 MB up; a 32nd otherwise: 2^24 fp32 keys, k = 2^20: 93 against
+    // 83 us; 1024 rows of 2^17 bf16 keys, k = 2^13: the sample declines, 298 against 273 us)
+    const bool big_f32 = dt == RTOPK_F32 && in_bytes >= ((int64_t)256 << 20);
     if (path == 2 && !scaling_on &&
-        (pre_knob == 1 || (pre_knob == 0 && k <= n / 32 &&
+        (pre_knob == 1 || (pre_knob == 0 && k <= n / (big_f32 ? 16 : 32) &&
                            (in_bytes >= ((int64_t)256 << 20) || (dt == RTOPK_F32 && in_bytes >= ((int64_t)64 << 20) && k * 4096 >= n))))) {
         c->prefilter = true;
         c->pre_stride = 31;
     }
     if (path == 2) {
         if (G == 0) {
-            // about two workgroups per compute unit in total; one when the sweep over X also counts and keeps
-            // little (measured on n = 2^28: k = 2^20 276 us with 256 workgroups, 305 with 512, 340 with 192 or
-            // 320; k = 2^22, where at least 1.6 % is kept, 426 against 377; two sweeps with k = 2^24: 641
-            // against 515)
+            // about two workgroups per compute unit in total; one for the fp32 sweep that counts and keeps, which
+            // then stages three times as much per wave (measured on n = 2^28: k = 2^20 239 us with 256 workgroups,
+            // 280 with 512, 298 with 384; k = 2^22 321 against 332; k = 2^24 389 against 395; two sweeps with
+            // k = 2^24: 603 against 526)
             // (16-bit keys: whole bins of an 11-bit digit are kept, more of the row; 2^29 fp16 keys, k = 2^20:
             // 260 us with 512, 346 with 256; bf16 with k = 50 or 2^10: no difference)
             // (and one for inputs that the caches hold: 2^24 fp32 keys, two sweeps: 53-61 us against 58-65; not
             // 128 MB: 2^26 fp16 keys of few distinct values, 355-385 us against 270-303)
             const bool cached = in_bytes <= ((int64_t)64 << 20);
-            int64_t want = ((c->prefilter && dt == RTOPK_F32 && k <= n / 256) || cached ? 256 : 512) / batch;
+            int64_t want = ((c->prefilter && dt == RTOPK_F32) || cached ? 256 : 512) / batch;
             if (want < 1) want = 1;
             G = (int)want;
         }
