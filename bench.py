@@ -61,6 +61,8 @@ def bytes_moved(tr, n, es, k):
         return 2 * es * n + first_wr + later + out, "one workgroup, two sweeps"
     if tr.pre_elems:                                       # sample + one sweep that counts and keeps
         b = es * tr.pre_elems + es * n + 8 * tr.pre_kept
+        if tr.pre_missed and tr.pre_merged:               # the sweep declined and counted two digits of the crowded bin:
+            return b + later + out, "sample + counting sweep, two-digit pass over X"   # pass 0 has no sweep of its own
         if tr.pre_missed:
             b += es * n + first_wr
             return b + later + out, "sample + counting sweep + second sweep"

@@ -237,8 +237,13 @@ typedef struct {
     uint32_t pre_merged;       /* 1: the prefilter's bound bin was the k-th key's bin, and pass 0 had no
                                   sweep of its own -- pass 1's sweep over what was kept classified by both
                                   digits at once (pass 0's record: its selectBin; winners are what lay above
-                                  its bin; neither read nor wrote anything)                           */
-    uint32_t reserved[7];
+                                  its bin; neither read nor wrote anything).  Also after a sweep that
+                                  declined (pre_missed 2), when the exact counts confirm pre_crowd and that
+                                  bin holds at least 7/8 of the row: both digits are then read from X    */
+    uint32_t pre_crowd;        /* with pre_bound = 2^bits (the sweep declined): the bin the sample puts the
+                                  k-th key in, whose elements' second digit the sweep counted as well;
+                                  0xffffffff if it counted none                                         */
+    uint32_t reserved[6];
     struct {
         uint32_t where;        /* 0 pass not run; 1 many workgroups; 2 single-workgroup finish;
                                   3 fused one-workgroup-per-row kernel; 4 one-sweep row kernel       */

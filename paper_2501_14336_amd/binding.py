@@ -69,7 +69,7 @@ class _PassRec(ctypes.Structure):
 
 
 class RtopkRowTrace(ctypes.Structure):
-    _fields_ = [("a_s", ctypes.c_float), ("error", ctypes.c_uint32), ("redo", ctypes.c_uint32), ("redo_why", ctypes.c_uint32), ("pre_elems", ctypes.c_uint32), ("pre_bound", ctypes.c_uint32), ("pre_kept", ctypes.c_uint32), ("pre_missed", ctypes.c_uint32), ("pre_merged", ctypes.c_uint32), ("reserved", ctypes.c_uint32 * 7),
+    _fields_ = [("a_s", ctypes.c_float), ("error", ctypes.c_uint32), ("redo", ctypes.c_uint32), ("redo_why", ctypes.c_uint32), ("pre_elems", ctypes.c_uint32), ("pre_bound", ctypes.c_uint32), ("pre_kept", ctypes.c_uint32), ("pre_missed", ctypes.c_uint32), ("pre_merged", ctypes.c_uint32), ("pre_crowd", ctypes.c_uint32), ("reserved", ctypes.c_uint32 * 6),
                 ("pass_rec", _PassRec * RTOPK_TRACE_MAX_PASSES)]
 
     @property

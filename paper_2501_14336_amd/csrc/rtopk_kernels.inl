@@ -713,6 +713,9 @@ struct NextCount {
                             // key above that digit equals only_bin, i.e. that lie in the sweep's bound bin
     HistSlot hist2{nullptr};
     u32 only_bin = 0, nan_shift = 0, nan_bin = 0;
+    // ... or, when the prefilter declined because the sample shows the keys crowded into one bin: the sweep itself counts
+    // digit `pi`, by raw bits, of every element whose raw first digit is crowd_raw, into hist2 (prefilter_tile_raw)
+    u32 crowd_raw = 0;
 };
 enum : u32 { kFlushToList = 1u, kFlushCount = 2u, kFlushNanFix = 4u, kFlushDiscard = 8u, kFlushCountIf = 16u };
 
@@ -946,7 +949,8 @@ __device__ __forceinline__ void inplace_tile_any(const Source& src, const typena
 // kept although they rank below the bound; pass 0 drops them like anything else below the k-th key's bin.  When
 // the prefilter declined, the edge is an infinity: only NaNs (and infinities of one sign) are staged, to have
 // their counts moved, and nothing is written.
-template <bool FULL, bool MERGE, bool LARGEST, class Source, int B, int ST>
+// CROWD: the sweep keeps nothing, and counts the next digit of the elements of one raw bin (see NextCount::crowd_raw).
+template <bool FULL, bool MERGE, bool LARGEST, bool CROWD = false, class Source, int B, int ST>
 __device__ __forceinline__ void prefilter_tile_raw(const Source& src, const typename Source::Tile& t, const DigitCtx& c,
                                                    const ClassifyOut<RTOPK_F32>& o, Shared<B, ST>& sm, u32 lane, u32 wave,
                                                    WriteState& ws, const NextCount& nc) {
@@ -965,6 +969,9 @@ __device__ __forceinline__ void prefilter_tile_raw(const Source& src, const type
         const u32 draw = raw >> c.pi.shift;
         if (FULL || valid) {
             if (MERGE) hist_add(hs, draw, lane); else hist_add_plain(hs, draw);
+        }
+        if (CROWD) {
+            if ((FULL || valid) && draw == nc.crowd_raw) hist_add(nc.hist2, (raw >> nc.pi.shift) & ((1u << nc.pi.bits) - 1u), lane);
         }
         const float x = __uint_as_float(raw);
         u64 m = ballot64(LARGEST ? !(x < o.t2) : !(x >= o.t2));
@@ -1002,7 +1009,8 @@ template <class Source, int DT, int SRC, int B, bool SINGLE, class Resident = No
 __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Params& P, int p, int row, u32 row_k, u32 wg, u32 G,
                                                     const PassEntry& e, rtopk_row_trace* st, float a_s, Shared<B, ST>& sm,
                                                     u32 where, const Selection& sel, u32 records, bool own_segment,
-                                                    const Resident& resident = Resident(), const Selection* sel0 = nullptr) {
+                                                    const Resident& resident = Resident(), const Selection* sel0 = nullptr,
+                                                    u32 crowd_bin = 0xffffffffu) {
     constexpr bool kResident = !std::is_same<Resident, NoResident>::value;
     static_assert(!PRE || (!SINGLE && !kResident && SRC != SRC_RUNTIME), "the prefilter is a grid sweep over X");
     DigitCtx ctx = make_digit_ctx(P, p, a_s);
@@ -1034,8 +1042,11 @@ __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Par
     const u32 wave = tid >> 6;
     const u32 ntiles = src.ntiles();
     // Leave the candidates where they are?  (Many workgroups per row only; see in-place passes.)
+    // (sel0: only when the two digits are read from X itself, the crowded case, where the rest of the key is likely
+    // to be just as crowded)
+    constexpr bool from_x = !std::is_same<Source, CandSource<B, kVecs>>::value;
     bool inplace = false;
-    if (!SINGLE && !PRE && !sel0 && !sel.emit_all && p + 1 < P.npass && sel.inside > P.small &&
+    if (!SINGLE && !PRE && (!sel0 || from_x) && !sel.emit_all && p + 1 < P.npass && sel.inside > P.small &&
         (u64)sel.inside * 8u > (u64)e.cand * 7u) {
         const PassInfo nx = P.pass[p + 1];
         const bool same = nx.src == own_pi.src && ctx.pi.bits + nx.bits <= 32u;    // the next digit extends this window
@@ -1048,7 +1059,6 @@ __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Par
 #endif
     u32 runW = e.out_before, runC = 0, myC = 0;
     // which candidate array this pass writes: the other one than it reads; array 0 from X; a prefilter sweep array 1
-    const bool from_x = !std::is_same<Source, CandSource<B, kVecs>>::value;
     const u32 out_array = PRE ? 1u : from_x ? 0u : 1u - e.src_array;
     const u32 rec_array = inplace ? e.src_array : out_array;
     const bool rec_inplace = inplace, rec_in_x = inplace && (from_x || e.src_in_x);
@@ -1089,11 +1099,13 @@ __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Par
     if (!PRE && wg == 0 && tid == 0) {
         if (sel0) {
             // pass 0's record: what its selectBin decided; its winners leave in this sweep
+            // (from X: the prefilter sweep kept nothing, the candidates of both passes are the row's own elements)
             PassEntry e0 = e;  // (only what a record takes from it matters)
-            e0.cand = st->pre_kept;
+            u32 cand0 = st->pre_kept;
+            if constexpr (from_x) cand0 = (u32)src.n;
+            e0.cand = cand0;
             e0.out_before = 0;
-            write_pass_record(st, 0, P.pass[0], e0, *sel0, where, e.src_array);
-            st->pass_rec[0].cand_before = st->pre_kept;
+            write_pass_record(st, 0, P.pass[0], e0, *sel0, where, e.src_array, from_x, from_x);
             st->pre_merged = 1u;
         }
         write_pass_record(st, p, own_pi, e, sel, where, rec_array, rec_inplace, rec_in_x);
@@ -1172,9 +1184,31 @@ __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Par
         }
     }
 
+    // The prefilter declined (keys crowded into few bins): if the sample's own bin for the k-th key is one that no
+    // NaN can fall into, the sweep also counts the next digit of that bin's elements, by raw bits.  Should the exact
+    // counts confirm the bin and it holds nearly the whole row, pass 0 then needs no sweep of its own: the launch after
+    // this one classifies X by both digits at once (k_pass0_after_prefilter).
+    bool crowd = false;
+    u32 crowd_raw = 0, crowd_flip = 0;
+    if constexpr (PRE && DT == RTOPK_F32 && SRC == SRC_KEY) {
+        const u32 maxd = (1u << ctx.pi.bits) - 1u, top = 1u << (ctx.pi.bits - 1u);
+        if (keep_none && crowd_bin <= maxd && pass_pair_is_one_window(P, p)) {
+            const bool largest = P.dirmask == 0;
+            const u32 dk = largest ? crowd_bin : maxd - crowd_bin;
+            crowd_raw = (dk & top) ? (dk & ~top) : (~dk & maxd);  // inverse of key_digit_of_raw
+            if ((crowd_raw & (top - 1u)) < (0x7f800000u >> ctx.pi.shift)) {
+                crowd = true;
+                // below the first digit the ordered key is the raw bits, complemented for negative elements, and once
+                // more for "smallest": one rule for the whole bin, whose elements share their sign
+                const bool negative = (crowd_raw & top) != 0;
+                crowd_flip = negative != !largest ? (1u << P.pass[p + 1].bits) - 1u : 0u;
+            }
+        }
+        if (wg == 0 && tid == 0) st->pre_crowd = crowd ? crowd_bin : 0xffffffffu;
+    }
     bool count_second = false;
     if constexpr (PRE) {
-        count_second = pass_pair_is_one_window(P, p) && sel.bin < (1u << ctx.pi.bits);
+        count_second = crowd || (pass_pair_is_one_window(P, p) && sel.bin < (1u << ctx.pi.bits));
         if (count_second)
             for (int j = tid; j < kMaxBins; j += B) sm.hist2[j] = 0;
     }
@@ -1201,10 +1235,11 @@ __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Par
     // The prefilter sweep counts pass p + 1's digit of what it keeps in its bound's bin, so that pass p needs no
     // sweep of its own when that bin turns out to be the k-th key's (see sel0).
     if (count_second) {
-        nc.count_if = true;
+        nc.count_if = !crowd;
         nc.hist2 = HistSlot{sm.hist2};
         nc.pi = P.pass[p + 1];
         nc.only_bin = sel.bin;
+        nc.crowd_raw = crowd_raw;
     }
     if (raw_pre) {
         nc.hist = HistSlot{sm.hist};
@@ -1230,14 +1265,19 @@ __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Par
         src, own_segment ? 0u : wg, own_segment ? 1u : G, ntiles,
         [&](const typename Source::Tile& cur) __attribute__((always_inline)) {
             if constexpr (PRE && DT == RTOPK_F32 && SRC == SRC_KEY) {
+                if (raw_pre && crowd) {
+                    if (P.dirmask == 0) prefilter_tile_raw<true, true, true, true, Source>(src, cur, ctx, o, sm, lane, wave, ws, nc);
+                    else prefilter_tile_raw<true, true, false, true, Source>(src, cur, ctx, o, sm, lane, wave, ws, nc);
+                    return;
+                }
                 if (raw_pre) {
                     const bool hot = hot_lanes<Source, DT, SRC>(src, cur, ctx) >= 12u;
                     if (P.dirmask == 0) {
-                        if (hot) prefilter_tile_raw<true, true, true, Source>(src, cur, ctx, o, sm, lane, wave, ws, nc);
-                        else prefilter_tile_raw<true, false, true, Source>(src, cur, ctx, o, sm, lane, wave, ws, nc);
+                        if (hot) prefilter_tile_raw<true, true, true, false, Source>(src, cur, ctx, o, sm, lane, wave, ws, nc);
+                        else prefilter_tile_raw<true, false, true, false, Source>(src, cur, ctx, o, sm, lane, wave, ws, nc);
                     } else {
-                        if (hot) prefilter_tile_raw<true, true, false, Source>(src, cur, ctx, o, sm, lane, wave, ws, nc);
-                        else prefilter_tile_raw<true, false, false, Source>(src, cur, ctx, o, sm, lane, wave, ws, nc);
+                        if (hot) prefilter_tile_raw<true, true, false, false, Source>(src, cur, ctx, o, sm, lane, wave, ws, nc);
+                        else prefilter_tile_raw<true, false, false, false, Source>(src, cur, ctx, o, sm, lane, wave, ws, nc);
                     }
                     return;
                 }
@@ -1271,9 +1311,14 @@ __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Par
         },
         [&](const typename Source::Tile& cur) __attribute__((always_inline)) {
             if constexpr (PRE && DT == RTOPK_F32 && SRC == SRC_KEY) {
+                if (raw_pre && crowd) {
+                    if (P.dirmask == 0) prefilter_tile_raw<false, true, true, true, Source>(src, cur, ctx, o, sm, lane, wave, ws, nc);
+                    else prefilter_tile_raw<false, true, false, true, Source>(src, cur, ctx, o, sm, lane, wave, ws, nc);
+                    return;
+                }
                 if (raw_pre) {
-                    if (P.dirmask == 0) prefilter_tile_raw<false, true, true, Source>(src, cur, ctx, o, sm, lane, wave, ws, nc);
-                    else prefilter_tile_raw<false, true, false, Source>(src, cur, ctx, o, sm, lane, wave, ws, nc);
+                    if (P.dirmask == 0) prefilter_tile_raw<false, true, true, false, Source>(src, cur, ctx, o, sm, lane, wave, ws, nc);
+                    else prefilter_tile_raw<false, true, false, false, Source>(src, cur, ctx, o, sm, lane, wave, ws, nc);
                     return;
                 }
             }
@@ -1340,6 +1385,23 @@ __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Par
         if (count_second) {
             // the second histogram of a prefilter sweep, published like the first, in buffers of its own
             const int nb2 = 1 << P.pass[pn + 1].bits;
+            if (crowd && crowd_flip != 0u) {
+                // counted by raw bits: move every count to the bin of its key digit
+                constexpr int kPer = kMaxBins / B;
+                u32 v[kPer];
+#pragma unroll
+                for (int i = 0; i < kPer; ++i) {
+                    const int j = (int)tid + i * B;
+                    v[i] = j < nb2 ? sm.hist2[j] : 0u;
+                }
+                __syncthreads();
+#pragma unroll
+                for (int i = 0; i < kPer; ++i) {
+                    const int j = (int)tid + i * B;
+                    if (j < nb2) sm.hist2[(u32)j ^ crowd_flip] = v[i];
+                }
+                __syncthreads();
+            }
             u32* g2 = hist_buffer(P, kHistSecond, row);
             for (int j = tid; j < nb2; j += B) {
                 const u32 c = sm.hist2[j];
@@ -1490,11 +1552,16 @@ __global__ void __launch_bounds__(kGridBlock) k_prefilter_keys(Params P) {
     // many duplicates --, writing that much out and reading it back costs more than the second sweep over X:
     // keep nothing (a bound above every bin), only count, and let pass 0 sweep X.
     constexpr u32 kCrowded = DT == RTOPK_F32 ? 8u : 16u;
-    if ((u64)(sel.above + sel.inside) * kCrowded > (u64)sample.elems) sel.bin = 1u << P.pass[0].bits;
+    u32 crowd_bin = 0xffffffffu;  // ... and say which bin the sample puts the k-th key in (see classify_phase: crowd)
+    if ((u64)(sel.above + sel.inside) * kCrowded > (u64)sample.elems) {
+        crowd_bin = sel.bin;
+        sel.bin = 1u << P.pass[0].bits;
+    }
     if (blockIdx.x == 0 && threadIdx.x == 0) st->pre_bound = sel.bin;
     e.k_rem = rs.k;
     classify_phase<decltype(src), DT, SRC, kGridBlock, false, NoResident, true>(src, P, 0, row, rs.k, blockIdx.x, gridDim.x, e, st,
-                                                                                st->a_s, sm, 1u, sel, gridDim.x, false);
+                                                                                st->a_s, sm, 1u, sel, gridDim.x, false,
+                                                                                NoResident(), nullptr, crowd_bin);
 }
 
 // Pass 0 after a prefilter sweep.  Every workgroup repeats selectBin on the exact counts that sweep left.  If the
@@ -1539,12 +1606,37 @@ __global__ void __launch_bounds__(kGridBlock) k_pass0_after_prefilter(Params P) 
                                                                               st->a_s, sm, 1u, sel, gridDim.x, true);
         }
     } else {
-        if (blockIdx.x == 0 && threadIdx.x == 0) st->pre_missed = bound == (1u << P.pass[0].bits) ? 2u : 1u;
+        const bool declined = bound == (1u << P.pass[0].bits);
+        if (blockIdx.x == 0 && threadIdx.x == 0) st->pre_missed = declined ? 2u : 1u;
         KeySource<DT, kGridBlock, key_vecs<DT>(), NT> src;
         src.init(rs);
         const u32 ntiles = src.ntiles();
-        classify_phase<decltype(src), DT, SRC_KEY, kGridBlock, false>(src, P, 0, row, rs.k, blockIdx.x, gridDim.x, e, st, st->a_s,
-                                                                      sm, 1u, sel, ntiles < gridDim.x ? ntiles : gridDim.x, false);
+        const u32 records = ntiles < gridDim.x ? ntiles : gridDim.x;
+        if (declined && st->pre_crowd == sel.bin && !sel.emit_all && pass_pair_is_one_window(P, 0) && sel.inside > P.small &&
+            (u64)sel.inside * 8u > (u64)e.cand * 7u) {
+            // The sweep declined to keep anything, named the bin the sample crowds into, and counted pass 1's digit for
+            // that bin; the exact counts confirm the bin and it holds nearly the whole row.  Pass 0 is then an in-place
+            // pass with no sweep, and pass 1 classifies X by both digits at once.
+            PassEntry e1;
+            e1.cand = sel.inside;
+            e1.k_rem = sel.k_inside;
+            e1.out_before = sel.above;
+            e1.finished = false;
+            e1.prev_multi = true;
+            e1.in_lds = false;
+            e1.src_array = 0u;
+            e1.src_in_x = true;
+            e1.chain = 1u;
+            __syncthreads();  // everybody has read the first selectBin's result: its LDS words may be reused
+            const Selection sel1 = select_pass<kGridBlock>(PlainCounts{hist_buffer(P, kHistSecond, row)}, 1 << P.pass[1].bits,
+                                                           e1, sm, st);
+            classify_phase<decltype(src), DT, SRC_RUNTIME, kGridBlock, false>(src, P, 1, row, rs.k, blockIdx.x, gridDim.x, e1, st,
+                                                                              st->a_s, sm, 1u, sel1, records, false, NoResident(),
+                                                                              &sel);
+        } else {
+            classify_phase<decltype(src), DT, SRC_KEY, kGridBlock, false>(src, P, 0, row, rs.k, blockIdx.x, gridDim.x, e, st,
+                                                                          st->a_s, sm, 1u, sel, records, false);
+        }
     }
 }
 

@@ -335,6 +335,36 @@ def test_prefilter_declines_when_the_keys_crowd_into_the_bins_to_keep():
                 assert tr.passes[0].cand_before == 300001
 
 
+def test_declined_prefilter_counts_two_digits_of_the_crowded_bin():
+    # The sweep that declines also counts the second digit of the bin the sample crowds into.  When the exact counts
+    # confirm that bin and it holds at least 7/8 of the row, pass 0 has no sweep of its own (an in-place pass whose
+    # record says: source X) and pass 1 classifies X by both digits at once.
+    T = dict(path=2, prefilter=1, small_threshold=64)
+    n = 300001
+    cases = [("narrow", W.narrow(n, 175)), ("negative narrow", -W.narrow(n, 176)),
+             ("all equal", np.full(n, np.float32(-2.5))), ("duplicates", W.duplicates(n, 177)),
+             ("two values", np.where(W.uniform01(n, 178) < 0.5, np.float32(3.0), np.float32(3.0000002)).astype(np.float32))]
+    for name, x in cases:
+        for k in (100, 20000, n - 5):
+            for largest in (True, False):
+                tr = _run_and_check("crowd " + name, x.view(np.uint32), F32, k, largest, tuning=T)[0]
+                if tr.pre_missed == 2 and tr.pre_merged:
+                    r0, r1 = tr.passes[0], tr.passes[1]
+                    assert tr.pre_crowd == r0.bin and r0.cand_before == n and (r0.window >> 25) & 3 == 3
+                    assert r0.cand_after * 8 > n * 7 and r1.cand_before == r0.cand_after
+    # the narrow range and the all-equal row do go that way
+    for x in (W.narrow(n, 175), np.full(n, np.float32(-2.5))):
+        tr = _run_and_check("crowd taken", x.view(np.uint32), F32, 1000, True, tuning=T)[0]
+        assert tr.pre_missed == 2 and tr.pre_merged == 1
+    # a crowd of infinities or NaNs: their bin can hold NaNs, which raw bits do not count right -- no second digit
+    for v in (np.inf, np.nan):
+        y = np.full(n, np.float32(v))
+        y[::7] = W.normal(n, 179)[::7]
+        for largest in (True, False):
+            tr = _run_and_check("crowd of specials", y.view(np.uint32), F32, 5000, largest, tuning=T)[0]
+            assert not (tr.pre_missed == 2 and tr.pre_merged)
+
+
 def test_prefilter_sample_holds_on_independent_draws():
     # On rows of independent draws the bin taken from the sample (with its margin) never lies above the k-th key's
     # bin: the second sweep stays unused, whatever k, and what is kept stays a small part of the row.
