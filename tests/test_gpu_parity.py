@@ -571,14 +571,21 @@ def test_kernels_stay_inside_the_workspace_and_the_outputs():
         (W.normal(5 * 8195, 88).astype(np.float16).view(np.uint16).reshape(5, 8195), F16, 17, dict(path=3)),
         (W.normal(3 * 300001, 89).view(np.uint32).reshape(3, 300001), F32, 256, dict(path=3)),
         (W.normal(70001, 90).view(np.uint32), F32, 35000, None),
+        (np.full(300001, np.float32(1.25)).view(np.uint32), F32, 777, dict(path=2, prefilter=1, small_threshold=64)),  # crowded bin
+        (W.llm_logits(5, 70001, 91), BF16, 400, dict(path=3)),                                       # sampled bound
+        (W.normal(100003, 92).view(np.uint32), F32, 20000, dict(path=2, sorted=True)),                # radix sort on the grid
+        (W.normal(3 * 20001, 93).view(np.uint32).reshape(3, 20001), F32, 8192, dict(path=1, sorted=True)),   # sort in LDS
     ]
     for bits, dtype, k, tuning in cases:
+        tuning = dict(tuning) if tuning else None
+        sorted_out = bool(tuning.pop("sorted", False)) if tuning else False
         for scaling in ((False, True) if dtype == F32 and not (tuning or {}).get("prefilter") else (False,)):
-            _say("guards:", bits.shape, dtype, k, tuning, "scaling", scaling)
+            _say("guards:", bits.shape, dtype, k, tuning, "scaling", scaling, "sorted", sorted_out)
             x = to_device(bits, dtype)
             batch, n = (1, bits.shape[0]) if bits.ndim == 1 else bits.shape
             es = 4 if dtype == F32 else 2
-            need = B.rtopk_workspace_bytes(batch, n, k, dtype, B.RTOPK_FLAG_SCALING if scaling else 0, tuning)
+            need = B.rtopk_workspace_bytes(batch, n, k, dtype, (B.RTOPK_FLAG_SCALING if scaling else 0) |
+                                           (B.RTOPK_FLAG_SORTED if sorted_out else 0), tuning)
             wbuf = torch.full((need + 2 * guard,), 0xA5, dtype=torch.uint8, device="cuda")
             vbuf = torch.full((batch * k * es + 2 * guard,), 0xA5, dtype=torch.uint8, device="cuda")
             ibuf = torch.full((batch * k * 8 + 2 * guard,), 0xA5, dtype=torch.uint8, device="cuda")
@@ -586,7 +593,8 @@ def test_kernels_stay_inside_the_workspace_and_the_outputs():
             ws = wbuf[guard:guard + need]
             vals = vbuf[guard:guard + batch * k * es].view(x.dtype).view(batch, k)
             idx = ibuf[guard:guard + batch * k * 8].view(torch.int64).view(batch, k)
-            B.topk(x, k, True, scaling=scaling, seed=3, tuning=tuning, workspace=ws, out=(vals, idx), check=True)
+            B.topk(x, k, True, scaling=scaling, seed=3, tuning=tuning, workspace=ws, out=(vals, idx), check=True,
+                   sorted=sorted_out)
             torch.cuda.synchronize()
             for name, buf, size in (("workspace", wbuf, need), ("values", vbuf, batch * k * es), ("indices", ibuf, batch * k * 8)):
                 assert bool((buf[:guard] == 0xA5).all()), "%s: bytes before the buffer were written" % name
