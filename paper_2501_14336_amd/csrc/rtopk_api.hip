@@ -44,8 +44,12 @@ static rtopk_status make_config(int64_t batch, int64_t n, int64_t k, rtopk_dtype
         if (tn->small_threshold) small = (u32)tn->small_threshold;
     }
     if (path == 0) {
-        // short rows, or enough rows to occupy every compute unit: one workgroup per row
-        path = (n <= (1 << 18) || (batch >= 256 && n <= (1 << 20))) ? 1 : 2;
+        // short rows, or enough rows to occupy the compute units: one workgroup per row.  (fp32, k = 16 or 1024, row
+        // kernel / grid kernels in us.  Uniform [0,1) keys, whose best bins are full: 1 x 2^15 32 / 36, 1 x 2^16
+        // 45 / 36, 16 x 2^16 47 / 39, 64 x 2^16 46 / 45, 128 x 2^16 49 / 55, 1 x 2^18 86 / 50, 16 x 2^18 87 / 60,
+        // 64 x 2^18 88 / 83, 128 x 2^18 90 / 107, 256 x 2^18 118 / 152.  Normal keys: 64 x 2^16 25 / 35,
+        // 128 x 2^17 40 / 67, 256 x 2^18 100 / 130.)
+        path = (n <= (1 << 16) || (batch >= 96 && n <= (1 << 18)) || (batch >= 256 && n <= (1 << 20))) ? 1 : 2;
         // ... unless a large part of every row is wanted: a workgroup that owns a row goes through its phases one
         // after the other (1024 rows of 2^17 bf16 keys, k = 8192: 51 + 36 us per row, 360 us in all), while the
         // grid kernels, one workgroup per row here, keep several rows per compute unit in flight (277 us; k = 2048:
@@ -54,15 +58,16 @@ static rtopk_status make_config(int64_t batch, int64_t n, int64_t k, rtopk_dtype
         if (batch > 65535) path = 1;
     }
     // The one-sweep kernel sets aside a few hundred elements of a row (its bound comes from the row's first
-    // eighth, more for larger k) and holds 2048; measured against the two-sweep kernels it wins from a few rows
-    // of 16K keys up, and on single long rows, as long as k is small.  Rows it cannot finish go to the two-sweep
-    // kernel, so the choice never changes the result.
+    // eighth, more for larger k) and holds 2048.  Rows it cannot finish go to the two-sweep kernel, so the choice
+    // never changes the result.
     bool one_sweep = path == 3;
     if (path == 3) path = 1;
     // (k up to 512 on rows of 64K keys up: the bound then comes from a sample of the row and is checked afterwards --
     // 1024 rows of 2^17 bf16 keys, k = 1024: see the measurements beside the kernel)
-    else if (path == 1 && (!tn || tn->path == 0) && (k <= 256 || (k <= 512 && n >= 65536)) && n >= 16384 &&
-             (batch >= 16 || n >= 131072))
+    // (against the two-sweep row kernel, fp32, k = 16, in us: normal keys 128 x 2^17 32 / 40, 256 x 2^17 41 / 57,
+    // 256 x 2^18 60 / 100, 512 x 2^17 63 / 102; uniform [0,1) keys, where the first part shows a full bin at the top and
+    // most rows are handed over: 256 x 2^16 61 / 55, 256 x 2^18 123 / 118)
+    else if (path == 1 && (!tn || tn->path == 0) && (k <= 256 || (k <= 512 && n >= 65536)) && n >= 16384 && batch >= 16)
         one_sweep = true;
     if (path == 2 && batch > 65535) return RTOPK_ERR_INVALID_ARG;  // rows are the grid's y dimension
     // 16-bit keys on long rows: a 12-bit first digit (4 bits left for the second) instead of 11 + 5 -- the first
@@ -87,15 +92,17 @@ static rtopk_status make_config(int64_t batch, int64_t n, int64_t k, rtopk_dtype
     const bool scaling_on = (flags & RTOPK_FLAG_SCALING) && dt == RTOPK_F32;
     // (inputs of 64 to 256 MB: two sweeps from the caches cost little more than one, and the call is bound by its
     // launches; for fp32 keys the prefilter still wins where pass 0 would otherwise write many candidates -- 2^24
-    // keys, k = 2^16: 62 against 82 us, k = 2^12: 61 against 65, k = 16: 61 against 58; 2^26 fp16 keys that all
-    // fall into one bin lost 100 us to the counting sweep that then stands before the two others)
+    // normal keys, k = 2^16: 62 against 82 us, k = 2^12: 61 against 65, k = 16: 61 against 56 -- and for batches,
+    // whatever k: 16 rows of 2^20, k = 16: 79 against 106; 64 rows of 2^20: 132 against 189; 2^26 fp16 keys that
+    // all fall into one bin lost 100 us to the counting sweep that then stands before the two others)
     const int64_t in_bytes = batch * n * eb;
     // (up to a sixteenth of the row for fp32 inputs of 256 MB up; a 32nd otherwise: 2^24 fp32 keys, k = 2^20: 93 against
     // 83 us; 1024 rows of 2^17 bf16 keys, k = 2^13: the sample declines, 298 against 273 us)
     const bool big_f32 = dt == RTOPK_F32 && in_bytes >= ((int64_t)256 << 20);
     if (path == 2 && !scaling_on &&
         (pre_knob == 1 || (pre_knob == 0 && k <= n / (big_f32 ? 16 : 32) &&
-                           (in_bytes >= ((int64_t)256 << 20) || (dt == RTOPK_F32 && in_bytes >= ((int64_t)64 << 20) && k * 4096 >= n))))) {
+                           (in_bytes >= ((int64_t)256 << 20) ||
+                            (dt == RTOPK_F32 && in_bytes >= ((int64_t)64 << 20) && (batch > 1 || k * 4096 >= n)))))) {
         c->prefilter = true;
         c->pre_stride = 31;
     }

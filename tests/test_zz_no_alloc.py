@@ -48,7 +48,7 @@ def test_static_scratch_matches_the_workspace_entry_point_twice_in_a_row():
     # matter to the second.  Shapes: one workgroup per row (registers, streaming, one sweep), many workgroups per
     # row (two sweeps and, forced by size, the later grid passes), ties, scaling.
     pairs = [
-        (lambda n: W.llm_logits(24, n, 91), BF16, (131072, 40001), 50, True, 0),
+        (lambda n: W.llm_logits(24, n, 91), BF16, (65536, 40001), 50, True, 0),
         (lambda n: W.normal(2 * n, 92).view(np.uint32).reshape(2, n), F32, (300001, 70001), 256, False, 0),
         (lambda n: W.normal(n, 93).view(np.uint32), F32, (2500001, 500001), 4096, True, 0),
         (lambda n: W.duplicates(n, 94).view(np.uint32), F32, (2000003, 300001), 150000, True, 0),
