@@ -45,6 +45,16 @@ def bytes_moved(tr, n, es, k):
             return 0
         src_in_x = i > 0 and (ps[i - 1].window >> 26) & 1
         rd = es * n if src_in_x else 8 * p.cand_before
+        if src_in_x and p.source == 2:
+            # an index digit read from X: only the positions its winners and its bin can have are read -- from the row's
+            # start up to the last position whose inverted index, taken from this digit up, is not below the chosen bin
+            # (with the bins of the index digits before it, all left in place, above it)
+            wide, q = p.bin, i - 1
+            while q >= 0 and ps[q].source == 2:
+                wide |= ps[q].bin << (ps[q].shift - p.shift)
+                q -= 1
+            idx_max = (1 << max(1, (n - 1).bit_length())) - 1
+            rd = es * max(0, min(n, idx_max - (wide << p.shift) + 1))
         if i > 0 and (ps[i - 1].window >> 25) & 1 and not src_in_x:
             q = i - 1                                      # the array the in-place chain reads is as long as when it was written
             while q > 0 and (ps[q - 1].window >> 25) & 1 and not (ps[q - 1].window >> 26) & 1:

@@ -885,19 +885,22 @@ __device__ __forceinline__ void classify_tile(const Source& src, const typename 
 // one's are taken from, fixed at compile time so that the slot loop holds no decisions: both from the key, both from
 // the scaled key, both from the index, or the key's last digit followed by the index's first.  KEY_EQ (index digits
 // after in-place key digits): only elements with the pivot's key count at all.
+// Full tiles first ask whether the crowd is total: if all 64 lanes' first elements are candidates with one and the same
+// next digit, the tile is taken a vector at a time -- a vector whose every element in every lane is such a candidate is
+// counted with one LDS add by one lane (no winners can be among them), any other vector goes the element-wise way.
+// (All keys equal, 2^28 fp32: an in-place sweep 340 -> see the measurements at the in-place passes.)
 template <bool FULL, int OWN, int NEXT, bool KEY_EQ, class Source, int DT, int B, int ST>
 __device__ __forceinline__ void inplace_tile(const Source& src, const typename Source::Tile& t, const DigitCtx& c,
                                              const ClassifyOut<DT>& o, Shared<B, ST>& sm, u32 lane, u32 wave, WriteState& ws,
                                              const NextCount& nc) {
     constexpr int S = Source::kSlots;
+    constexpr int E = Source::E;
     uint2* st = sm.stage[wave];
     const u64 me_bit = 1ull << lane;
     const u32 wmask = c.pi.bits >= 32u ? 0xffffffffu : (1u << c.pi.bits) - 1u;
     const u32 nmask = (1u << nc.pi.bits) - 1u;
-#pragma unroll
-    for (int s = 0; s < S; ++s) {
-        if (s % kStageGroup == 0) make_room<DT, false>(o, sm, lane, wave, ws, nc);  // (winners are few: a call will do)
-        u32 raw, idx;
+    // one element: is it a candidate (cand), its window digit (wd) and its next digit (nd)
+    auto look = [&](int s, u32& raw, u32& idx, u32& wd, u32& nd, bool& ok) __attribute__((always_inline)) {
         bool valid;
         src.get(t, s, raw, idx, valid);
         u32 u;  // the 32 bits this pass's digit is a window of
@@ -907,19 +910,55 @@ __device__ __forceinline__ void inplace_tile(const Source& src, const typename S
             u = KeyOf<DT>::key(raw) ^ c.dirmask;
         else
             u = KeyOf<RTOPK_F32>::key(__float_as_uint(__uint_as_float(raw) - c.a_s)) ^ c.dirmask;
-        const u32 wd = (u >> c.pi.shift) & wmask;
-        bool ok = FULL || valid;
+        wd = (u >> c.pi.shift) & wmask;
+        ok = FULL || valid;
         if (KEY_EQ) ok = ok && (KeyOf<DT>::key(raw) ^ c.dirmask) == o.key_eq;
+        const u32 v = NEXT == OWN ? u : c.idx_max - idx;
+        nd = (v >> nc.pi.shift) & nmask;
+    };
+    auto slot = [&](int s) __attribute__((always_inline)) {
+        if (s % kStageGroup == 0) make_room<DT, false>(o, sm, lane, wave, ws, nc);  // (winners are few: a call will do)
+        u32 raw, idx, wd, nd;
+        bool ok;
+        look(s, raw, idx, wd, nd, ok);
         const u64 mw = ballot64(ok && wd >= o.wmin && wd <= o.wmax);
         const u64 mc = ballot64(ok && wd == o.b);
-        if (mc & me_bit) {
-            const u32 v = NEXT == OWN ? u : c.idx_max - idx;
-            hist_add(nc.hist, (v >> nc.pi.shift) & nmask, lane);
-        }
+        if (mc & me_bit) hist_add(nc.hist, nd, lane);
         if (mw) {
             if (mw & me_bit) st[ws.fillW + mbcnt64(mw)] = make_uint2(raw, idx);
             ws.fillW += (u32)__popcll(mw);
         }
+    };
+    bool total = false;
+    if constexpr (FULL) {
+        u32 raw, idx, wd, nd;
+        bool ok;
+        look(0, raw, idx, wd, nd, ok);
+        total = ballot64(ok && wd == o.b && nd == (u32)__builtin_amdgcn_readfirstlane(nd)) == ~0ull;
+    }
+    if (FULL && total) {
+#pragma unroll
+        for (int v = 0; v < S / E; ++v) {
+            bool all = true;
+            u32 d0 = 0;
+#pragma unroll
+            for (int j = 0; j < E; ++j) {
+                u32 raw, idx, wd, nd;
+                bool ok;
+                look(v * E + j, raw, idx, wd, nd, ok);
+                if (j == 0) d0 = (u32)__builtin_amdgcn_readfirstlane(nd);
+                all = all && ok && wd == o.b && nd == d0;
+            }
+            if (ballot64(all) == ~0ull) {
+                if (lane == 0) atomicAdd(nc.hist.at(d0), 64u * (u32)E);
+            } else {
+#pragma unroll
+                for (int j = 0; j < E; ++j) slot(v * E + j);
+            }
+        }
+    } else {
+#pragma unroll
+        for (int s = 0; s < S; ++s) slot(s);
     }
 }
 // ... with OWN / NEXT / KEY_EQ taken from the pass at run time, once per tile.
@@ -959,8 +998,7 @@ __device__ __forceinline__ void prefilter_tile_raw(const Source& src, const type
     uint2* st = sm.stage[wave];
     const u64 me_bit = 1ull << lane;
     const HistSlot hs{sm.hist};
-#pragma unroll
-    for (int s = 0; s < S; ++s) {
+    auto slot = [&](int s) __attribute__((always_inline)) {
         // (sparse by design: the room made between tiles nearly always suffices, so this one may be a call)
         if (s % kStageGroup == 0) make_room<RTOPK_F32, false>(o, sm, lane, wave, ws, nc);
         u32 raw, idx;
@@ -980,7 +1018,39 @@ __device__ __forceinline__ void prefilter_tile_raw(const Source& src, const type
             if (m & me_bit) st[(u32)(ST - 1) - (ws.fillC + mbcnt64(m))] = make_uint2(raw, idx);
             ws.fillC += (u32)__popcll(m);
         }
+    };
+    // CROWD, full tiles: a vector whose every element, in every lane, lies in the crowded bin with one and the same
+    // next digit is counted by one lane with two LDS adds (the bin can hold neither NaN nor infinity: nothing to
+    // stage).  Tried for the tiles whose first vector is of that kind (a narrow range of many values never is, and
+    // pays nothing for the question beyond that one look).
+    if constexpr (CROWD && FULL) {
+        const u32 nmask = (1u << nc.pi.bits) - 1u;
+        const u32 sh = nc.pi.shift;
+        auto total = [&](int v, u32& d0) __attribute__((always_inline)) {
+            const uint4 q = t.r[v];
+            d0 = (u32)__builtin_amdgcn_readfirstlane((q.x >> sh) & nmask);
+            const u32 hi = (nc.crowd_raw << (c.pi.shift - sh)) | d0;  // both digits, as the top bits of the element
+            return ballot64((q.x >> sh) == hi && (q.y >> sh) == hi && (q.z >> sh) == hi && (q.w >> sh) == hi) == ~0ull;
+        };
+        u32 d0;
+        if (total(0, d0)) {
+#pragma unroll
+            for (int v = 0; v < S / 4; ++v) {
+                if (total(v, d0)) {
+                    if (lane == 0) {
+                        atomicAdd(hs.at(nc.crowd_raw), 256u);
+                        atomicAdd(nc.hist2.at(d0), 256u);
+                    }
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) slot(v * 4 + j);
+                }
+            }
+            return;
+        }
     }
+#pragma unroll
+    for (int s = 0; s < S; ++s) slot(s);
 }
 
 // Where the histogram of a pass is.
@@ -1224,6 +1294,26 @@ __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Par
     t_pro = wall_clock64();
     if (p == 0) RTOPK_STAMP(8);
 #endif
+    // An index digit read from X itself (every pass before it left its candidates in place): the digit window reaches
+    // up to the top of the inverted index, so what this pass can still want -- its winners and its bin -- are the
+    // elements of one stretch of positions, and only the tiles that cover it are read (ties at the k-th key go to the
+    // lowest positions: all keys equal, 2^28 of them, k = 2^20: the first 2^20 elements of the row instead of all).
+    u32 tile_lo = 0u, tile_hi = 0xffffffffu;
+    if constexpr (from_x && !PRE && !SINGLE && SRC == SRC_RUNTIME) {
+        if (own_pi.src == SRC_IDX && ctx.pi.shift + ctx.pi.bits >= 32u - (u32)__builtin_clz(ctx.idx_max | 1u)) {
+            const bool none_above = o.wmin > o.wmax;
+            const u64 w_lo = none_above || o.b < o.wmin ? o.b : o.wmin, w_hi = none_above || o.b > o.wmax ? o.b : o.wmax;
+            const u64 u_lo = w_lo << ctx.pi.shift, u_top = ((w_hi + 1u) << ctx.pi.shift) - 1u;
+            const u64 u_hi = u_top < (u64)ctx.idx_max ? u_top : (u64)ctx.idx_max;
+            if (u_lo <= u_hi) {
+                const u64 tile_elems = (u64)B * Source::kSlots;
+                const u64 pos_lo = (u64)ctx.idx_max - u_hi + src.lead, pos_hi = (u64)ctx.idx_max - u_lo + src.lead;
+                tile_lo = (u32)(pos_lo / tile_elems);
+                const u64 th = pos_hi / tile_elems + 1u;
+                tile_hi = th < 0xffffffffull ? (u32)th : 0xffffffffu;
+            }
+        }
+    }
     WriteState ws;
     ws.fillW = ws.fillC = 0;
     NextCount nc;
@@ -1330,7 +1420,7 @@ __device__ __forceinline__ PassEntry classify_phase(const Source& src, const Par
             }
             classify_tile<false, false, Source, DT, SRC, B, false, PRE, true>(src, cur, ctx, o, sm, lane, wave, ws, nc);
         },
-        0u, 0xffffffffu,
+        tile_lo, tile_hi,
         [&]() __attribute__((always_inline)) {
             if (ws.fillW + ws.fillC > (u32)ST - kStageEarlyRoom) flush_staged<DT, true>(o, sm, lane, wave, ws, nc);
         });
