@@ -352,6 +352,16 @@ def test_declined_prefilter_counts_two_digits_of_the_crowded_bin():
                     r0, r1 = tr.passes[0], tr.passes[1]
                     assert tr.pre_crowd == r0.bin and r0.cand_before == n and (r0.window >> 25) & 3 == 3
                     assert r0.cand_after * 8 > n * 7 and r1.cand_before == r0.cand_after
+    # rows that start off the 16-byte grid (the index digits read from X are bounded by position: lead-in included),
+    # several rows, 16-bit keys too
+    m = 70001
+    dup = W.duplicates(3 * m, 180)
+    T2 = dict(path=2, small_threshold=64)
+    for k in (50, 30000, m - 3):
+        for largest in (True, False):
+            _run_and_check("in place, odd rows", dup.view(np.uint32).reshape(3, m), F32, k, largest, tuning=T2)
+            _run_and_check("in place, odd rows bf16", W.to_bf16_bits(dup).reshape(3, m), BF16, k, largest, tuning=T2)
+            _run_and_check("in place, equal rows f16", np.full((3, m), np.float16(1.0)).view(np.uint16), F16, k, largest, tuning=T2)
     # the narrow range and the all-equal row do go that way
     for x in (W.narrow(n, 175), np.full(n, np.float32(-2.5))):
         tr = _run_and_check("crowd taken", x.view(np.uint32), F32, 1000, True, tuning=T)[0]
