@@ -86,7 +86,7 @@ def bytes_moved(tr, n, es, k):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--log2n", type=int, default=28, help="row length 2^log2n (default: the headline 2^28)")
     ap.add_argument("--log2k", type=int, default=20)
@@ -142,9 +142,9 @@ def main() -> int:
         B.topk(x, k, True, workspace=ws, out=(vals, idx))
     torch.cuda.synchronize()
 
-    # ---- timed region: exactly `steps` steps.  On every 4th step the library records 5 HIP events on the
+    # ---- timed region: exactly `steps` steps.  On every 10th step the library records 5 HIP events on the
     # launch stream around the two big kernels (an event costs a few microseconds of stream time, so not on all).
-    sampled = [i for i in range(steps) if i % 4 == 0]
+    sampled = [i for i in range(steps) if i % 10 == 0]
     per_step = {i: make_events(B.RTOPK_NUM_EVENTS) for i in sampled}
     torch.cuda.synchronize()
     t0 = time.perf_counter()
