@@ -54,7 +54,7 @@ static rtopk_status make_config(int64_t batch, int64_t n, int64_t k, rtopk_dtype
         // after the other (1024 rows of 2^17 bf16 keys, k = 8192: 51 + 36 us per row, 360 us in all), while the
         // grid kernels, one workgroup per row here, keep several rows per compute unit in flight (277 us; k = 2048:
         // 281 against 230, k = 1024: 217 against 224)
-        if (path == 1 && batch >= 256 && batch <= 65535 && n >= 65536 && k * 64 >= n) path = 2;
+        if (path == 1 && batch >= 256 && batch <= 65535 && n >= 65536 && k * 128 >= n) path = 2;
         if (batch > 65535) path = 1;
     }
     // The one-sweep kernel sets aside a few hundred elements of a row (its bound comes from the row's first
@@ -73,7 +73,9 @@ static rtopk_status make_config(int64_t batch, int64_t n, int64_t k, rtopk_dtype
     // 16-bit keys on long rows: a 12-bit first digit (4 bits left for the second) instead of 11 + 5 -- the first
     // sweep then keeps a bin of half the width (bf16 logits, 64 x 2^22, k = 50: 200 -> 167 us; 2^29 uniform bf16
     // keys: 1052 -> 788 us); the one-workgroup-per-row kernels stay at 11, where twice the histogram copies fit
-    if (path == 2 && dt != RTOPK_F32 && !(tn && tn->digit_bits)) d = 12;
+    // (not where one workgroup has a whole row of such a batch and k is small: 1024 rows of 2^17 bf16 keys, 11 against
+    // 12 bits: k = 1024 203 against 222 us, k = 2048 222 against 230, k = 4096 290 both, k = 8192 283 against 276)
+    if (path == 2 && dt != RTOPK_F32 && !(tn && tn->digit_bits) && !(batch >= 256 && k * 32 <= n)) d = 12;
     const int eb = elem_bytes(dt);
     const int64_t tile_elems = (int64_t)kHostGridBlock * kHostElemsPerLane;  // 16 elements per lane for every type
     const int64_t ntiles = (n + 16 / eb - 1 + tile_elems) / tile_elems;  // one spare for the lead-in
