@@ -37,6 +37,36 @@ __device__ __forceinline__ u32 load_value(const void* v, size_t i) {
     return DT == RTOPK_F32 ? ((const u32*)v)[i] : (u32)((const uint16_t*)v)[i];
 }
 
+// Up to three consecutive levels of the bitonic network (strides S, S/2, ... down to h = S >> (L - 1)) in one go:
+// the 2^L elements that these levels connect -- h apart, starting at a multiple of 2 S plus an offset below h -- are
+// held by one thread, which exchanges among them in registers.  One barrier and one trip through LDS per group of
+// levels instead of one per level.  (All of a group's elements lie in one block of `size` elements: one direction.)
+template <int L>
+__device__ __forceinline__ void bitonic_levels(u64* buf, u32 m, u32 size, u32 S, u32 tid) {
+    constexpr u32 N = 1u << L;
+    const u32 h = S >> (L - 1);
+    for (u32 g = tid; g < (m >> L); g += kRowBlock) {
+        const u32 base = (g / h) * (h << L) + (g & (h - 1u));
+        const bool up = (base & size) == 0;
+        u64 e[N];
+#pragma unroll
+        for (u32 j = 0; j < N; ++j) e[j] = buf[base + j * h];
+#pragma unroll
+        for (int l = L - 1; l >= 0; --l) {
+#pragma unroll
+            for (u32 j = 0; j < N; ++j) {
+                if ((j >> l) & 1u) continue;
+                const u64 a = e[j], b = e[j | (1u << l)];
+                const bool swap = (a > b) == up;
+                e[j] = swap ? b : a;
+                e[j | (1u << l)] = swap ? a : b;
+            }
+        }
+#pragma unroll
+        for (u32 j = 0; j < N; ++j) buf[base + j * h] = e[j];
+    }
+}
+
 // k <= kSortSmall: bitonic sort of one row's keys in LDS.
 template <int DT>
 __global__ void __launch_bounds__(kRowBlock) k_sort_small(Params P) {
@@ -54,19 +84,18 @@ __global__ void __launch_bounds__(kRowBlock) k_sort_small(Params P) {
     while (m < k) m <<= 1;
     for (u32 i = tid; i < m; i += B)
         buf[i] = i < k ? sort_key_of<DT>(load_value<DT>(out_v, i), (u32)out_i[i], P.dirmask) : ~0ull;  // padding sorts last
-    for (u32 size = 2; size <= m; size <<= 1) {
-        for (u32 stride = size >> 1; stride > 0; stride >>= 1) {
+    for (u32 size = 2, levels = 1; size <= m; size <<= 1, ++levels) {
+        // the levels of this size, largest stride first: a first group of levels % 3 (if any), then groups of three,
+        // so that the group with the smallest strides -- the one whose threads touch neighbouring words -- is a full one
+        u32 stride = size >> 1, left = levels;
+        while (left > 0) {
+            const u32 L = left % 3u ? left % 3u : 3u;
             __syncthreads();
-            for (u32 t = tid; t < m / 2; t += B) {
-                const u32 i = 2 * t - (t & (stride - 1));
-                const u32 j = i + stride;
-                const bool up = (i & size) == 0;
-                const u64 a = buf[i], b = buf[j];
-                if ((a > b) == up) {
-                    buf[i] = b;
-                    buf[j] = a;
-                }
-            }
+            if (L == 1) bitonic_levels<1>(buf, m, size, stride, tid);
+            else if (L == 2) bitonic_levels<2>(buf, m, size, stride, tid);
+            else bitonic_levels<3>(buf, m, size, stride, tid);
+            stride >>= L;
+            left -= L;
         }
     }
     __syncthreads();
