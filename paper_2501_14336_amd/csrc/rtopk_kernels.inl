@@ -1561,9 +1561,11 @@ __global__ void __launch_bounds__(256) k_init(Params P) {
     const int row = blockIdx.x;
     // (the sample's histogram and the second digit's exist only with the prefilter sweep)
     const int buffers = P.pre_stride != 0 ? kHostHistBuffers : kHistRing;
+    int bins = 1;  // (as many bins as the widest digit has: with many rows this clearing is the launch's whole time)
+    for (int p = 0; p < P.npass; ++p) bins = bins > (1 << P.pass[p].bits) ? bins : 1 << P.pass[p].bits;
     for (int h = 0; h < buffers; ++h) {
         u32* ghist = P.ghist + ((size_t)h * P.batch + row) * kMaxBins;
-        for (int j = threadIdx.x; j < kMaxBins; j += 256) ghist[j] = 0;
+        for (int j = threadIdx.x; j < bins; j += 256) ghist[j] = 0;
     }
     init_row<DT>(P, row, row_state(P, row), row_shape<KeyOf<DT>::kBytes>(P, row));
 }
