@@ -66,8 +66,9 @@ static rtopk_status make_config(int64_t batch, int64_t n, int64_t k, rtopk_dtype
     // 1024 rows of 2^17 bf16 keys, k = 1024: see the measurements beside the kernel)
     // (against the two-sweep row kernel, fp32, k = 16, in us: normal keys 128 x 2^17 32 / 40, 256 x 2^17 41 / 57,
     // 256 x 2^18 60 / 100, 512 x 2^17 63 / 102; uniform [0,1) keys, where the first part shows a full bin at the top and
-    // most rows are handed over: 256 x 2^16 61 / 55, 256 x 2^18 123 / 118)
-    else if (path == 1 && (!tn || tn->path == 0) && (k <= 256 || (k <= 512 && n >= 65536)) && n >= 16384 && batch >= 16)
+    // most rows are handed over: 256 x 2^16 61 / 55, 256 x 2^18 123 / 118.  With fewer rows than a quarter of the
+    // compute units there is nothing to overlap: 16 x 2^16 uniform keys 47 / 41, 64 x 2^16 normal keys 24 / 25.)
+    else if (path == 1 && (!tn || tn->path == 0) && (k <= 256 || (k <= 512 && n >= 65536)) && n >= 16384 && batch >= 64)
         one_sweep = true;
     if (path == 2 && batch > 65535) return RTOPK_ERR_INVALID_ARG;  // rows are the grid's y dimension
     // 16-bit keys on long rows: a 12-bit first digit (4 bits left for the second) instead of 11 + 5 -- the first
