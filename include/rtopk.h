@@ -76,7 +76,7 @@ typedef struct {
                                 handles a row)                                                                  */
     int32_t path;            /* 0 auto, 1 one workgroup per row (fused kernel), 2 many workgroups per row,
                                 3 like 1, with the one-sweep kernel for small k first (auto picks it for
-                                large batches of rows with k <= 256)                                            */
+                                batches of 64 rows up with k <= 256, k <= 512 on rows of 64K keys up)           */
     int32_t wgs_per_row;     /* workgroups cooperating on one row in path 2 (default: fill 256 CUs)            */
     int32_t small_threshold; /* candidate count at or below which one workgroup finishes a row by itself       */
     int32_t prefilter;       /* path 2: 0 auto, 1 always, -1 never: histogram of a sample of the row, then ONE
