@@ -200,7 +200,9 @@ def main() -> int:
         except Exception:
             traffic = None
 
-    whole_frac = path_bytes / (call_ms * 1e-3) / 1e9 / HBM_PEAK_GBS
+    # the whole call: the timed region's own time per step (calls back to back on one stream; the steps that carry
+    # the library's five event markers run about 10 us longer, see gpu_ms_per_marked_call)
+    whole_frac = path_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS
     out = {
         "metric": "top-k keys/sec (single query n=2^28 fp32, k=2^20) and % of HBM peak BW",
         "value": keys_per_s,
@@ -222,15 +224,16 @@ def main() -> int:
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_src,
                      "kernel_ms": dominant[1], "algorithmic_bytes": dominant[2],
                      "whole_call_frac": whole_frac, "whole_call_target_0.60_met": bool(whole_frac >= 0.60)},
-        "whole_path": {"gpu_ms_per_call": call_ms, names[0] + "_ms": hist_ms, names[1] + "_ms": classify_ms,
+        "whole_path": {"ms_per_call": ms_per_step, "gpu_ms_per_marked_call": call_ms, names[0] + "_ms": hist_ms,
+                       names[1] + "_ms": classify_ms,
                        "structure": path_kind, "elements_counted_before_the_sweep": tr.pre_elems if prefilter else n,
                        "bytes_moved_by_all_passes": path_bytes,
                        "achieved_frac_of_hbm_peak": whole_frac,
                        "sample_misled": bool(tr.pre_missed) if prefilter else None,
                        "one_read_floor_bytes": floor1_bytes,
-                       "one_read_floor_frac_of_hbm_peak": floor1_bytes / (call_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                       "one_read_floor_frac_of_hbm_peak": floor1_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
                        "two_sweep_floor_bytes": floor_bytes,
-                       "two_sweep_floor_frac_of_hbm_peak": floor_bytes / (call_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                       "two_sweep_floor_frac_of_hbm_peak": floor_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
                        "passes": [[p.where, p.cand_before, p.cand_after, p.winners] for p in tr.passes]},
     }
 
@@ -303,7 +306,7 @@ def main() -> int:
             name = "C4 k=2^%d" % lk
             if lk == args.log2k:
                 rows.append({"config": name, "batch": 1, "n": n, "k": k, "dtype": "f32", "largest": True, "scaling": False,
-                             "ms": call_ms, "keys_per_s": n / (call_ms * 1e-3), "structure": path_kind,
+                             "ms": ms_per_step, "keys_per_s": n / (ms_per_step * 1e-3), "structure": path_kind,
                              "bytes_moved": path_bytes, "frac_of_hbm_peak_on_bytes_moved": whole_frac,
                              "note": "the headline, from the timed region above"})
             elif wanted(name) and args.log2n == 28:
@@ -311,7 +314,7 @@ def main() -> int:
                 rows.append(e)
         if wanted("C4 sorted") and args.log2n == 28:
             med, best, _, wsb, _, _ = time_rows(x, k, True, False, B.RTOPK_F32, 1, n, reps=5, sorted_out=True, wsb=wsb)
-            rows.append({"config": "C4 sorted k=2^%d" % args.log2k, "ms": med, "sort_share_of_call": 1.0 - call_ms / med,
+            rows.append({"config": "C4 sorted k=2^%d" % args.log2k, "ms": med, "sort_share_of_call": 1.0 - ms_per_step / med,
                          "note": "radix sort of the k pairs on the grid after the selection"})
         del wsb, x, ws, vals, idx
         torch.cuda.empty_cache()
